@@ -1,0 +1,165 @@
+"""Scheduler oracle: which workgroup runs which MAC-loop iterations.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).  Integer arithmetic in plain
+Python, one step per passage of the paper, no blocking or shortcuts.
+
+What it follows
+---------------
+* Algorithm 1 (Sec. 3.1): iterations per tile, total iterations, the equal
+  split of the iteration space over g workgroups, and the outer loop that cuts a
+  workgroup's range at output-tile boundaries.
+* Sec. 3.2: the all-Stream-K schedule (everything is split, no data-parallel
+  work) and the hybrids, where a "batch" is one trip of Algorithm 1's outer loop
+  for every workgroup, i.e. at most one tile's worth of iterations each.
+* Sec. 4.1: a persistent grid of g workgroups; Stream-K batches (zero to six) are
+  issued first and data-parallel batches after them, so the fix-up latency of
+  the split tiles hides under data-parallel work.
+* Sec. 5.3: the fix-up by partial results plus inter-workgroup synchronisation
+  (instead of atomic adds); that is where OWNER / CONTRIB roles come from.
+
+Readings taken where the paper is silent or ambiguous
+-----------------------------------------------------
+R1  The seven policies are b = 0 (pure data-parallel), b = 1..5 Stream-K batches
+    followed by data-parallel batches, and all-Stream-K.  b = 6 is kept as an
+    eighth, extension id.
+R2  With W = T div g full waves and rem = T mod g leftover tiles, b Stream-K
+    batches cover sk_tiles = min(T, rem + (b-1)*g) tiles ("one batch" = the
+    remainder wave, "two batches" = remainder plus one full wave, Sec. 3.2).
+    If rem = 0 and b = 1 nothing is left over, so the schedule equals pure DP.
+R3  The Stream-K tiles are the lowest tile indices [0, sk_tiles); the
+    data-parallel tiles follow and workgroup x takes sk_tiles + x + j*g.
+R4  Algorithm 1 does not clamp a workgroup's range to the iteration total; both
+    ends are clamped here (trailing workgroups may be empty).  The split is the
+    paper's ceil split, not a balanced one.
+R5  Tile index -> coordinates is row-major over the tile grid.
+R6  The workgroup whose segment holds a tile's k-iteration 0 owns the tile; the
+    others store an fp32 partial in workspace slot = their workgroup id and the
+    owner adds them in ascending workgroup order (= ascending k).
+"""
+from collections import namedtuple
+
+POLICY_NAMES = ("DP", "SK1_DP", "SK2_DP", "SK3_DP", "SK4_DP", "SK5_DP", "ALL_SK", "SK6_DP_EXT")
+POLICY_DP, POLICY_SK1_DP, POLICY_SK2_DP, POLICY_SK3_DP = 0, 1, 2, 3
+POLICY_SK4_DP, POLICY_SK5_DP, POLICY_ALL_SK, POLICY_SK6_DP_EXT = 4, 5, 6, 7
+SEVEN_POLICIES = (0, 1, 2, 3, 4, 5, 6)
+
+ROLE_FULL, ROLE_OWNER, ROLE_CONTRIB = 0, 1, 2
+
+Segment = namedtuple("Segment", "wg tile k_begin k_end role")
+WgRange = namedtuple("WgRange", "sk_iter_begin sk_iter_end dp_tile_first dp_tile_count")
+Plan = namedtuple("Plan", "header ranges segments")
+
+
+def cdiv(a, b):
+    return -(-a // b)
+
+
+def decompose(M, N, K, blk_m, blk_n, blk_k):
+    """Algorithm 1, lines 2-3: tile grid, iterations per tile, total iterations."""
+    tiles_m = cdiv(M, blk_m)
+    tiles_n = cdiv(N, blk_n)
+    iters_per_tile = cdiv(K, blk_k)
+    tiles = tiles_m * tiles_n
+    return tiles_m, tiles_n, tiles, iters_per_tile, tiles * iters_per_tile
+
+
+def sk_batches(policy):
+    """Number of Stream-K batches b of a policy; None means all-Stream-K (Sec. 3.2, 4.1)."""
+    if policy == POLICY_ALL_SK:
+        return None
+    if policy == POLICY_SK6_DP_EXT:
+        return 6
+    if 0 <= policy <= 5:
+        return policy
+    raise ValueError("unknown policy %r" % (policy,))
+
+
+def sk_tile_count(tiles, g, policy):
+    """How many output tiles are handed to the Stream-K region (reading R2)."""
+    b = sk_batches(policy)
+    if b is None:
+        return tiles
+    if b == 0:
+        return 0
+    rem = tiles % g
+    return min(tiles, rem + (b - 1) * g)
+
+
+def tile_coords(tile, tiles_n):
+    """Row-major tile index -> (tile_m, tile_n) (reading R5)."""
+    return tile // tiles_n, tile % tiles_n
+
+
+def wg_sk_range(x, sk_iters, iters_per_wg):
+    """Algorithm 1, lines 5-6, clamped to the Stream-K iteration total (reading R4)."""
+    begin = min(x * iters_per_wg, sk_iters)
+    end = min((x + 1) * iters_per_wg, sk_iters)
+    return begin, end
+
+
+def wg_sk_segments(x, begin, end, iters_per_tile):
+    """Algorithm 1, lines 7-20: cut [begin, end) at tile boundaries."""
+    segs = []
+    it = begin
+    while it < end:
+        tile = it // iters_per_tile
+        tile_iter = tile * iters_per_tile
+        tile_iter_end = tile_iter + iters_per_tile
+        local_iter = it - tile_iter
+        local_iter_end = min(end, tile_iter_end) - tile_iter
+        if local_iter > 0:
+            role = ROLE_CONTRIB
+        elif local_iter_end < iters_per_tile:
+            role = ROLE_OWNER
+        else:
+            role = ROLE_FULL
+        segs.append(Segment(x, tile, local_iter, local_iter_end, role))
+        it = tile_iter_end
+    return segs
+
+
+def plan(M, N, K, policy, blk_m, blk_n, blk_k, g):
+    """Full schedule for one problem: header, per-workgroup ranges, canonical segment list.
+
+    The segment list is ordered by workgroup, and inside a workgroup in execution
+    order: Stream-K segments ascending, then data-parallel tiles ascending
+    (Sec. 3.2 / 4.1: Stream-K batches come first).
+    """
+    if min(M, N, K, blk_m, blk_n, blk_k, g) < 1:
+        raise ValueError("sizes must be positive")
+    tiles_m, tiles_n, tiles, ipt, total = decompose(M, N, K, blk_m, blk_n, blk_k)
+    sk_tiles = sk_tile_count(tiles, g, policy)
+    dp_tiles = tiles - sk_tiles
+    sk_iters = sk_tiles * ipt
+    ipw = cdiv(sk_iters, g)                       # Algorithm 1, line 4, on the SK region
+    ranges, segments = [], []
+    for x in range(g):
+        begin, end = wg_sk_range(x, sk_iters, ipw)
+        segs = wg_sk_segments(x, begin, end, ipt)
+        first = sk_tiles + x
+        count = cdiv(tiles - first, g) if first < tiles else 0
+        for j in range(count):
+            segs.append(Segment(x, first + j * g, 0, ipt, ROLE_FULL))
+        ranges.append(WgRange(begin, end, first if count else tiles, count))
+        segments.extend(segs)
+    header = dict(M=M, N=N, K=K, policy=policy, blk_m=blk_m, blk_n=blk_n, blk_k=blk_k, grid=g,
+                  tiles_m=tiles_m, tiles_n=tiles_n, tiles=tiles, iters_per_tile=ipt,
+                  total_iters=total, sk_tiles=sk_tiles, dp_tiles=dp_tiles, sk_iters=sk_iters,
+                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g))
+    return Plan(header, ranges, segments)
+
+
+def contributors(p, owner_segment):
+    """Workgroups whose partials the owner of a split tile adds, in reduction order (R6)."""
+    ipt, ipw = p.header["iters_per_tile"], p.header["iters_per_wg"]
+    assert owner_segment.role == ROLE_OWNER
+    last = (owner_segment.tile * ipt + ipt - 1) // ipw
+    return list(range(owner_segment.wg + 1, last + 1))
+
+
+def makespan_iters(p):
+    """MAC-loop iterations executed by the busiest workgroup."""
+    load = [0] * p.header["grid"]
+    for s in p.segments:
+        load[s.wg] += s.k_end - s.k_begin
+    return max(load)
