@@ -1,0 +1,162 @@
+"""Benchmark of the Stream-K++ hot path on one MI355X.
+
+A step is one pass of the whole path for one GEMM: query the Bloom filters for the problem size,
+take the surviving policy that the tuning pass timed fastest, and run sk_gemm under that policy's
+plan.  Before the timed region a tuning pass times all seven policies (50 warm-up + 50 timed
+launches each, the paper's protocol, Sec. 5.1) and builds the filters from the policies within 20 %
+of the best (Sec. 4.2).  Inputs are seeded synthetic matrices already resident in HBM.
+
+Prints ONE JSON line: TFLOP/s of the Bloom-selected policy, the MFMA roofline of the GEMM kernel
+(HIP events around each launch, on the launch stream) and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6}    # dense MFMA peak of MI355X
+
+
+def workload(name):
+    from paper_2408_11417_amd import inputs
+    if name == "cfg2":
+        c = inputs.config2()
+        c["label"] = "cfg2: bf16 GEMM 3840x4224x4096, 256x128x64 tiles (495 tiles, 1.93 waves), N(0,1)/sqrt(K), seed 1"
+    elif name == "cfg5":
+        c = inputs.config5(inputs.BF16)
+        c["label"] = "cfg5: bf16 GEMM 8192^3, U[-1,1], seed 3"
+    elif name == "cfg1":
+        c = inputs.config1()
+        c["label"] = "cfg1: fp16 GEMM 512^3, 128x128x32 tiles, U[-1,1], seed 0"
+    elif name.startswith("cfg3"):
+        c = inputs.config3(int(name.split("_")[1]))
+        c["label"] = "cfg3: bf16 skinny GEMM M=%d N=K=8192, N(0,0.02), seed 2" % c["M"]
+    else:
+        raise SystemExit("unknown workload %r" % name)
+    return c
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--policy", type=int, default=-1, help="skip tuning and run this policy only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures the single-GPU Stream-K GEMM; --gpus must be 1 (got %d)" % args.gpus)
+
+    import torch
+    import paper_2408_11417_amd as sk
+
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    c = workload(args.workload)
+    M, N, K, dt = c["M"], c["N"], c["K"], c["dtype"]
+    dtype_name = {0: "f16", 1: "bf16"}[dt]
+    flops = 2.0 * M * N * K
+    dA = torch.from_numpy(c["A"].view(np.int16)).cuda()
+    dB = torch.from_numpy(c["B"].view(np.int16)).cuda()
+    D = torch.empty((M, N), dtype=torch.int16, device="cuda")
+
+    plans, keep = {}, []
+    for p in range(sk.SK_NUM_POLICIES):
+        plan = sk.sk_plan(M, N, K, p, c["blk"], c["grid"], dt, c["out_dtype"])
+        nbytes = sk.sk_workspace_bytes(plan)
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        sk.sk_plan_set_workspace(plan, (ws.data_ptr() + 255) // 256 * 256, nbytes)
+        keep.append(ws)
+        plans[p] = plan
+    info = sk.sk_plan_info(plans[0])
+
+    def launch(p):
+        sk.sk_gemm(dA.data_ptr(), dB.data_ptr(), D.data_ptr(), plans[p], stream)
+
+    def time_policy(p, warm, timed):
+        for _ in range(warm):
+            launch(p)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(timed)]
+        for e0, e1 in evs:
+            e0.record()
+            launch(p)
+            e1.record()
+        torch.cuda.synchronize()
+        return float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))   # ms per launch
+
+    # ---- tuning pass (untimed): all seven policies, then the Bloom filters from the winners
+    if args.policy >= 0:
+        t_pol = {args.policy: time_policy(args.policy, 10, 10)}
+    else:
+        t_pol = {p: time_policy(p, 50, 50) for p in range(sk.SK_NUM_POLICIES)}
+    best = min(t_pol.values())
+    mask = sum(1 << p for p, t in t_pol.items() if t <= 1.2 * best)
+    bloom = sk.bloom_build([(M, N, K, mask)])
+
+    def step():
+        cand = sk.bloom_query(bloom, M, N, K)
+        sel = min((p for p in t_pol if (cand >> p) & 1), key=lambda p: t_pol[p])
+        launch(sel)
+        return sel
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record()
+        sel = step()
+        e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert sk.sk_plan_check(plans[sel], stream) == sk.SK_OK
+    kernel_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    ms_per_step = wall * 1e3 / args.steps
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (kernel_ms * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[dtype_name]
+
+    out = {
+        "metric": "gemm_tflops_bloom_selected_policy", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype_name,
+        "data": "synthetic",
+        "config": {"workload": c["label"], "M": M, "N": N, "K": K,
+                   "tile": [info["blk_m"], info["blk_n"], info["blk_k"]], "grid": info["grid"]},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(achieved / peak, 4), "traffic": None,
+                     "kernel": "streamk_gemm_kernel", "kernel_ms": round(kernel_ms, 5)},
+        "selected_policy": sk.POLICY_NAMES[sel],
+        "selected_over_best": round(best / t_pol[sel], 4),
+        "policies_tflops": {sk.POLICY_NAMES[p]: round(flops / (t * 1e-3) / 1e12, 2) for p, t in t_pol.items()},
+        "bloom_candidates": [sk.POLICY_NAMES[p] for p in t_pol if (mask >> p) & 1],
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import gemm as G
+        from paper_2408_11417_amd import inputs
+        odt = G.F16 if dt == 0 else G.BF16
+        probe_rows = inputs.sample_rows(M, min(M, 8), 0)
+        t0 = time.perf_counter()
+        G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows)
+        per_row = (time.perf_counter() - t0) / len(probe_rows)
+        n_rows = int(max(8, min(M, 12.0 / max(per_row, 1e-9))))
+        rows = inputs.sample_rows(M, n_rows, 1)
+        t0 = time.perf_counter()
+        G.gemm_fp64(c["A"], c["B"], odt, rows=rows)
+        dt_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * len(rows) * N * K / dt_cpu / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": G.threads(), "kind": "oracle",
+                               "sample": "%d of %d rows of D (all N columns, full K), %.1f s" % (len(rows), M, dt_cpu)}
+    print(json.dumps(out), flush=True)
+    for p in plans.values():
+        sk.sk_plan_destroy(p)
+    sk.bloom_destroy(bloom)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,217 @@
+/* streamk.h - C ABI of the MI355X Stream-K++ GEMM library (libstreamk.so).
+ *
+ * The library computes D = A * B (fp16 / bf16 / fp8-e4m3 inputs, fp32
+ * accumulation) with the work of all output tiles - tiles x K-iterations of the
+ * MAC loop - divided over a persistent grid of workgroups under one of the
+ * Stream-K++ scheduling policies, and holds the Bloom-filter selector that
+ * prunes policies for a problem size.  Citations are to the paper
+ * "Stream-K++: Adaptive GPU GEMM Kernel Selection and Scheduling for AI using
+ * Bloom Filters" (arXiv 2408.11417).
+ *
+ * Conventions for every entry point
+ *  - returns an sk_status (0 = ok, negative = error); nothing throws or aborts
+ *    across this boundary; out-parameters are left untouched on error;
+ *  - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *    device memory of the current device, at least 16-byte aligned;
+ *  - the caller owns A, B, D, the workspace and the stream; the library owns
+ *    the opaque sk_plan_t / sk_bloom_t objects (create / destroy pairs);
+ *  - matrices are dense row-major: A is M x K (leading dimension K), B is K x N
+ *    (leading dimension N), D is M x N (leading dimension N).
+ */
+#ifndef STREAMK_H
+#define STREAMK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SK_OK = 0,
+    SK_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, unknown enum value       */
+    SK_ERR_UNSUPPORTED = -2,  /* no kernel for this tile / dtype, or grid cannot be resident */
+    SK_ERR_WORKSPACE = -3,    /* workspace missing or too small                             */
+    SK_ERR_HIP = -4,          /* a HIP runtime call failed                                  */
+    SK_ERR_NOMEM = -5,        /* host allocation failed                                     */
+    SK_ERR_TIMEOUT = -6       /* a tile owner gave up waiting for a partial (see sk_plan_check) */
+} sk_status;
+
+/* The seven scheduling policies (Sec. 3.2, Sec. 4.1): b Stream-K batches issued
+ * first, data-parallel batches after them.  b = 0 is the conventional
+ * data-parallel schedule (Sec. 1), ALL_SK is Algorithm 1 applied to every tile.
+ * One Stream-K batch is one trip of Algorithm 1's outer loop per workgroup, so
+ * b batches cover the remainder wave (tiles mod grid) plus b-1 full waves of
+ * tiles, clamped to the tile count.  SK6_DP_EXT (b = 6) is an extension beyond
+ * the seven. */
+typedef enum {
+    SK_POLICY_DP = 0,
+    SK_POLICY_SK1_DP = 1,
+    SK_POLICY_SK2_DP = 2,
+    SK_POLICY_SK3_DP = 3,
+    SK_POLICY_SK4_DP = 4,
+    SK_POLICY_SK5_DP = 5,
+    SK_POLICY_ALL_SK = 6,
+    SK_POLICY_SK6_DP_EXT = 7
+} sk_policy;
+#define SK_NUM_POLICIES 7
+
+typedef enum { SK_F16 = 0, SK_BF16 = 1, SK_FP8_E4M3 = 2, SK_F32 = 3 /* output only */ } sk_dtype;
+
+/* Role of a segment in the fix-up (Sec. 5.3: partial results combined under
+ * inter-workgroup synchronisation instead of Algorithm 1's atomic adds). */
+typedef enum {
+    SK_ROLE_FULL = 0,    /* all K-iterations of the tile: store D directly                      */
+    SK_ROLE_OWNER = 1,   /* holds K-iteration 0: waits for the contributors, reduces, stores D  */
+    SK_ROLE_CONTRIB = 2  /* starts after K-iteration 0: stores an fp32 partial tile and signals */
+} sk_role;
+
+/* Tile shape, grid and types.  A zero field means "library default": the tile
+ * is then chosen from (M, N, K), grid = 256 (one workgroup per compute unit),
+ * in_dtype = SK_BF16, out_dtype = in_dtype (SK_BF16 for fp8 inputs). */
+typedef struct {
+    int32_t blk_m, blk_n, blk_k;
+    int32_t grid;
+    int32_t in_dtype;   /* sk_dtype + 1, or 0 for default */
+    int32_t out_dtype;  /* sk_dtype + 1, or 0 for default */
+} sk_config;
+
+/* Numbers of Algorithm 1, lines 2-4, and of the Stream-K / data-parallel split. */
+typedef struct {
+    int64_t M, N, K;
+    int32_t policy;
+    int32_t blk_m, blk_n, blk_k, grid;
+    int32_t in_dtype, out_dtype;          /* sk_dtype values */
+    int32_t tiles_m, tiles_n, tiles;      /* ceil(M/blk_m), ceil(N/blk_n), their product    */
+    int32_t iters_per_tile;               /* ceil(K/blk_k)                                  */
+    int64_t total_iters;                  /* tiles * iters_per_tile                         */
+    int32_t sk_tiles, dp_tiles;           /* tiles [0, sk_tiles) are split, the rest are not */
+    int64_t sk_iters;                     /* sk_tiles * iters_per_tile                      */
+    int32_t iters_per_wg;                 /* ceil(sk_iters / grid)                          */
+    int32_t dp_waves;                     /* ceil(dp_tiles / grid)                          */
+    int32_t has_kernel;                   /* 1 if sk_gemm has a kernel for this tile + dtype */
+} sk_plan_header;
+
+/* Work of one workgroup x: global Stream-K iterations [sk_iter_begin, sk_iter_end)
+ * (Algorithm 1, lines 5-6, clamped to sk_iters), then data-parallel tiles
+ * dp_tile_first + j*grid for j in [0, dp_tile_count). */
+typedef struct {
+    int64_t sk_iter_begin, sk_iter_end;
+    int32_t dp_tile_first, dp_tile_count;
+} sk_wg_range;
+
+/* One MAC-loop call (Algorithm 1, lines 8-13): workgroup wg runs K-iterations
+ * [k_begin, k_end) of tile `tile`.  Tile t covers rows (t / tiles_n) * blk_m ...
+ * and columns (t % tiles_n) * blk_n ... of D. */
+typedef struct {
+    int32_t wg, tile, k_begin, k_end, role;
+} sk_segment;
+
+typedef struct sk_plan_t sk_plan_t;
+
+/* Build the schedule of one problem under one policy (Algorithm 1, lines 2-6;
+ * Sec. 3.2; Sec. 4.1).  Host only, no device contact.  cfg may be NULL (all
+ * defaults).  Any positive tile shape is accepted for planning; whether sk_gemm
+ * can run it is reported in sk_plan_header.has_kernel.
+ * Errors: INVALID_ARG (sizes < 1, unknown policy / dtype, totals beyond int32
+ * tiles or int64 iterations), NOMEM. */
+int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_config* cfg, sk_plan_t** out);
+
+/* Copy the plan's numbers to host memory. */
+int sk_plan_info(const sk_plan_t* plan, sk_plan_header* out);
+
+/* Per-workgroup iteration ranges: out is host memory for `grid` entries. */
+int sk_plan_ranges(const sk_plan_t* plan, sk_wg_range* out);
+
+/* Canonical expansion of the schedule: segments ordered by workgroup and, inside
+ * a workgroup, in execution order (Stream-K segments, then data-parallel tiles;
+ * Sec. 4.1).  out is host memory for `cap` entries (may be NULL when cap = 0);
+ * *n receives the number of segments; INVALID_ARG if cap is too small (then *n
+ * still receives the needed count). */
+int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t cap, size_t* n);
+
+/* Device bytes sk_gemm needs for this plan: one flag line per workgroup, a
+ * status word, and one fp32 partial tile (blk_m * blk_n) per workgroup.
+ * Returns 0 for a NULL plan. */
+size_t sk_workspace_bytes(const sk_plan_t* plan);
+
+/* Attach caller-owned device memory (>= sk_workspace_bytes, 256-byte aligned).
+ * Clears the flag and status area with a blocking memset on the null stream.
+ * One workspace must not serve two launches that are in flight at once; it may
+ * be shared by plans that run one after another on one stream.
+ * Errors: INVALID_ARG, WORKSPACE (too small / misaligned), HIP. */
+int sk_plan_set_workspace(sk_plan_t* plan, void* dev_ptr, size_t bytes);
+
+/* Number of flag polls after which a waiting tile owner gives up, records a
+ * time-out in the workspace status word and goes on (so that every wave exits
+ * even if a partial never arrives).  Default 1 << 24.  0 = give up on the first
+ * unsuccessful poll (for tests of the error path). */
+int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls);
+
+/* D = A * B under the plan (Algorithm 1 with its MAC loop on the matrix cores;
+ * Sec. 4.1 persistent grid; fix-up per Sec. 5.3).  A, B, D: device pointers in
+ * the plan's dtypes and the row-major layout stated above.  stream: a
+ * hipStream_t (NULL = the null stream).  Asynchronous: enqueues one kernel and
+ * returns; never synchronises.  D is fully overwritten.
+ * Errors: INVALID_ARG, UNSUPPORTED (no kernel for tile + dtype, or the grid
+ * cannot be co-resident while the plan has split tiles), WORKSPACE (plan has
+ * split tiles but no workspace), HIP (launch failed). */
+int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream);
+
+/* Blocking: waits for `stream`, reads the workspace status word and clears it.
+ * Returns SK_OK, or SK_ERR_TIMEOUT if any launch since the last check gave up
+ * waiting for a partial tile. */
+int sk_plan_check(const sk_plan_t* plan, void* stream);
+
+void sk_plan_destroy(sk_plan_t* plan);
+
+/* The tile shape the library picks for (M, N, K, in_dtype) when sk_config leaves
+ * it zero.  out_blk: host int32[3] = blk_m, blk_n, blk_k. */
+int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_blk);
+
+/* ---- Bloom-filter policy selector (Sec. 4.2) --------------------------------
+ * One filter per policy.  A record says which policies are winners for a
+ * problem size; the size is inserted into the filter of each of them.  A query
+ * returns the policies whose filter may contain the size: an inserted policy is
+ * never missing from the answer (no false negatives).
+ * Key: MurmurHash3 (32-bit) over M, N, K as three little-endian uint32; filter p
+ * probes k bits with seeds p*k + i; bit j is bit (j % 64) of word (j / 64). */
+typedef struct {
+    uint32_t M, N, K;
+    uint32_t policy_mask;   /* bit p set: policy p is a winner for this size */
+} sk_bloom_record;
+
+typedef struct {
+    uint32_t m_bits;     /* bits per filter, multiple of 64; 0 = 95872 (10 000 sizes at ~1 %) */
+    uint32_t k_probes;   /* probes per filter; 0 = 7                                          */
+    uint32_t n_filters;  /* 0 = 7 (one per policy); at most 32                                */
+} sk_bloom_params;
+
+typedef struct sk_bloom_t sk_bloom_t;
+
+/* Build the filters from n records (host memory; n may be 0).  params may be NULL. */
+int bloom_build(const sk_bloom_record* recs, size_t n, const sk_bloom_params* params, sk_bloom_t** out);
+
+/* Insert one more record into existing filters. */
+int bloom_insert(sk_bloom_t* bloom, const sk_bloom_record* rec);
+
+/* Candidate policies for (M, N, K): bit p of *mask_out is set iff filter p holds all probe bits.
+ * Sizes must fit uint32 (INVALID_ARG otherwise). */
+int bloom_query(const sk_bloom_t* bloom, int64_t M, int64_t N, int64_t K, uint32_t* mask_out);
+
+/* Read access to filter `filter`: *words points at library-owned 64-bit words, valid until
+ * bloom_destroy; *n_words = m_bits / 64. */
+int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** words, size_t* n_words);
+
+/* The hash itself (exported for known-answer tests). */
+uint32_t bloom_murmur3_32(const void* key, size_t len, uint32_t seed);
+
+void bloom_destroy(sk_bloom_t* bloom);
+
+const char* sk_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STREAMK_H */

@@ -1,0 +1,122 @@
+// Bloom-filter policy selector (Sec. 4.2): one bit array per scheduling policy,
+// keyed by a 32-bit Murmur3 hash of the problem size.  Host code, integers only.
+#include <cstring>
+#include <new>
+#include <vector>
+#include "streamk.h"
+
+struct sk_bloom_t {
+    uint32_t m_bits, k_probes, n_filters;
+    std::vector<std::vector<uint64_t>> filters;
+};
+
+namespace {
+
+inline uint32_t rotl(uint32_t v, int r) { return (v << r) | (v >> (32 - r)); }
+
+inline uint32_t scramble(uint32_t k) {
+    k *= 0xCC9E2D51u;
+    k = rotl(k, 15);
+    return k * 0x1B873593u;
+}
+
+inline uint32_t avalanche(uint32_t h) {
+    h ^= h >> 16; h *= 0x85EBCA6Bu;
+    h ^= h >> 13; h *= 0xC2B2AE35u;
+    return h ^ (h >> 16);
+}
+
+uint32_t murmur3(const uint8_t* p, size_t len, uint32_t seed) {
+    uint32_t h = seed;
+    size_t i = 0;
+    for (; i + 4 <= len; i += 4) {
+        const uint32_t k = (uint32_t)p[i] | (uint32_t)p[i + 1] << 8 | (uint32_t)p[i + 2] << 16 | (uint32_t)p[i + 3] << 24;
+        h = rotl(h ^ scramble(k), 13) * 5u + 0xE6546B64u;
+    }
+    if (i < len) {
+        uint32_t k = 0;
+        for (size_t j = len; j-- > i;) k = (k << 8) | p[j];
+        h ^= scramble(k);
+    }
+    return avalanche(h ^ (uint32_t)len);
+}
+
+// Three-word key specialisation of the same hash (no tail, length 12).
+inline uint32_t hash_key(uint32_t M, uint32_t N, uint32_t K, uint32_t seed) {
+    uint32_t h = seed;
+    h = rotl(h ^ scramble(M), 13) * 5u + 0xE6546B64u;
+    h = rotl(h ^ scramble(N), 13) * 5u + 0xE6546B64u;
+    h = rotl(h ^ scramble(K), 13) * 5u + 0xE6546B64u;
+    return avalanche(h ^ 12u);
+}
+
+void insert(sk_bloom_t* b, const sk_bloom_record& r) {
+    for (uint32_t p = 0; p < b->n_filters; p++) {
+        if (!((r.policy_mask >> p) & 1u)) continue;
+        for (uint32_t i = 0; i < b->k_probes; i++) {
+            const uint32_t bit = hash_key(r.M, r.N, r.K, p * b->k_probes + i) % b->m_bits;
+            b->filters[p][bit >> 6] |= (uint64_t)1 << (bit & 63);
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" uint32_t bloom_murmur3_32(const void* key, size_t len, uint32_t seed) {
+    return murmur3(static_cast<const uint8_t*>(key), key ? len : 0, seed);
+}
+
+extern "C" int bloom_build(const sk_bloom_record* recs, size_t n, const sk_bloom_params* params, sk_bloom_t** out) {
+    if (!out || (!recs && n)) return SK_ERR_INVALID_ARG;
+    sk_bloom_params p{};
+    if (params) p = *params;
+    if (!p.m_bits) p.m_bits = 95872;
+    if (!p.k_probes) p.k_probes = 7;
+    if (!p.n_filters) p.n_filters = SK_NUM_POLICIES;
+    if (p.m_bits % 64 || p.n_filters > 32 || p.k_probes > 64) return SK_ERR_INVALID_ARG;
+    sk_bloom_t* b = new (std::nothrow) sk_bloom_t;
+    if (!b) return SK_ERR_NOMEM;
+    b->m_bits = p.m_bits; b->k_probes = p.k_probes; b->n_filters = p.n_filters;
+    try {
+        b->filters.assign(p.n_filters, std::vector<uint64_t>(p.m_bits / 64, 0));
+    } catch (const std::bad_alloc&) {
+        delete b;
+        return SK_ERR_NOMEM;
+    }
+    for (size_t i = 0; i < n; i++) insert(b, recs[i]);
+    *out = b;
+    return SK_OK;
+}
+
+extern "C" int bloom_insert(sk_bloom_t* bloom, const sk_bloom_record* rec) {
+    if (!bloom || !rec) return SK_ERR_INVALID_ARG;
+    insert(bloom, *rec);
+    return SK_OK;
+}
+
+extern "C" int bloom_query(const sk_bloom_t* bloom, int64_t M, int64_t N, int64_t K, uint32_t* mask_out) {
+    if (!bloom || !mask_out) return SK_ERR_INVALID_ARG;
+    const int64_t lim = 0xFFFFFFFFll;
+    if (M < 0 || N < 0 || K < 0 || M > lim || N > lim || K > lim) return SK_ERR_INVALID_ARG;
+    uint32_t mask = 0;
+    for (uint32_t p = 0; p < bloom->n_filters; p++) {
+        const uint64_t* w = bloom->filters[p].data();
+        bool hit = true;
+        for (uint32_t i = 0; i < bloom->k_probes && hit; i++) {
+            const uint32_t bit = hash_key((uint32_t)M, (uint32_t)N, (uint32_t)K, p * bloom->k_probes + i) % bloom->m_bits;
+            hit = (w[bit >> 6] >> (bit & 63)) & 1u;
+        }
+        if (hit) mask |= 1u << p;
+    }
+    *mask_out = mask;
+    return SK_OK;
+}
+
+extern "C" int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** words, size_t* n_words) {
+    if (!bloom || !words || !n_words || filter < 0 || (uint32_t)filter >= bloom->n_filters) return SK_ERR_INVALID_ARG;
+    *words = bloom->filters[filter].data();
+    *n_words = bloom->filters[filter].size();
+    return SK_OK;
+}
+
+extern "C" void bloom_destroy(sk_bloom_t* bloom) { delete bloom; }

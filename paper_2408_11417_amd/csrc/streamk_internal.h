@@ -1,0 +1,21 @@
+// Internal definitions shared by the host planner and the HIP launcher.
+#pragma once
+#include <cstdint>
+#include <cstddef>
+#include "streamk.h"
+
+struct sk_plan_t {
+    sk_plan_header h;
+    void* workspace = nullptr;      // caller-owned device memory
+    size_t workspace_bytes = 0;
+    uint32_t spin_limit = 1u << 24;
+    int needs_fixup = 0;            // 1 if any tile is split over several workgroups
+};
+
+// Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]
+constexpr size_t SK_FLAG_STRIDE = 128;
+inline size_t sk_ws_status_offset(int grid) { return (size_t)grid * SK_FLAG_STRIDE; }
+inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_FLAG_STRIDE + 128; }
+
+// Does the GEMM launcher hold a kernel for this configuration?
+bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k);

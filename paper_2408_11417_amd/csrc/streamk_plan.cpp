@@ -1,0 +1,193 @@
+// Host-side scheduler: turns (M, N, K, policy, tile, grid) into the numbers the
+// persistent kernel walks, and expands them into the canonical segment list.
+// Integer arithmetic only; no device contact.
+#include <cstdlib>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <vector>
+#include "streamk_internal.h"
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Stream-K batches of a policy: 0..6, or -1 for "every tile is split" (Sec. 3.2).
+int batches_of(int policy) {
+    switch (policy) {
+    case SK_POLICY_ALL_SK: return -1;
+    case SK_POLICY_SK6_DP_EXT: return 6;
+    default: return policy;   // DP .. SK5_DP carry their batch count as enum value
+    }
+}
+
+bool dtype_in_ok(int d) { return d == SK_F16 || d == SK_BF16 || d == SK_FP8_E4M3; }
+bool dtype_out_ok(int d) { return d == SK_F16 || d == SK_BF16 || d == SK_F32; }
+
+// Segments of workgroup x, appended in execution order.
+void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_wg_range* range) {
+    const int64_t ipt = h.iters_per_tile;
+    int64_t it = x * (int64_t)h.iters_per_wg;
+    int64_t end = it + h.iters_per_wg;
+    if (it > h.sk_iters) it = h.sk_iters;
+    if (end > h.sk_iters) end = h.sk_iters;
+    if (range) { range->sk_iter_begin = it; range->sk_iter_end = end; }
+    // Algorithm 1, lines 7-20: one segment per tile the range touches
+    while (it < end) {
+        const int64_t tile = it / ipt;
+        const int64_t tile_first = tile * ipt;
+        const int64_t stop = (end < tile_first + ipt) ? end : tile_first + ipt;
+        sk_segment s;
+        s.wg = x;
+        s.tile = (int32_t)tile;
+        s.k_begin = (int32_t)(it - tile_first);
+        s.k_end = (int32_t)(stop - tile_first);
+        s.role = s.k_begin > 0 ? SK_ROLE_CONTRIB : (s.k_end < ipt ? SK_ROLE_OWNER : SK_ROLE_FULL);
+        if (out) out->push_back(s);
+        it = tile_first + ipt;
+    }
+    // data-parallel tiles follow the Stream-K work (Sec. 4.1)
+    int32_t count = 0;
+    for (int64_t t = (int64_t)h.sk_tiles + x; t < h.tiles; t += h.grid) {
+        if (out) out->push_back(sk_segment{x, (int32_t)t, 0, (int32_t)ipt, SK_ROLE_FULL});
+        ++count;
+    }
+    if (range) {
+        range->dp_tile_count = count;
+        range->dp_tile_first = count ? h.sk_tiles + x : h.tiles;
+    }
+}
+
+}  // namespace
+
+extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_blk) {
+    if (!out_blk || M < 1 || N < 1 || K < 1 || !dtype_in_ok(in_dtype)) return SK_ERR_INVALID_ARG;
+    // Dispatcher heuristic: big tiles when there are enough of them to fill 256 compute
+    // units, smaller ones otherwise; skinny M gets a tile as tall as M.
+    int bm, bn, bk = 64;
+    if (M <= 16) { bm = 16; bn = 128; }
+    else if (M <= 32) { bm = 32; bn = 128; }
+    else if (M <= 64) { bm = 64; bn = 128; }
+    else {
+        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
+        const int64_t t256x128 = ceil_div(M, 256) * ceil_div(N, 128);
+        if (t256 >= 512 && N > 128) { bm = 256; bn = 256; }
+        else if (t256x128 >= 256 && M > 128) { bm = 256; bn = 128; }
+        else { bm = 128; bn = 128; }
+    }
+    (void)K;
+    out_blk[0] = bm; out_blk[1] = bn; out_blk[2] = bk;
+    return SK_OK;
+}
+
+extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_config* cfg, sk_plan_t** out) {
+    if (!out || M < 1 || N < 1 || K < 1) return SK_ERR_INVALID_ARG;
+    if (policy < 0 || policy > SK_POLICY_SK6_DP_EXT) return SK_ERR_INVALID_ARG;
+    sk_config c{};
+    if (cfg) c = *cfg;
+    if (c.blk_m < 0 || c.blk_n < 0 || c.blk_k < 0 || c.grid < 0) return SK_ERR_INVALID_ARG;
+    const int in_dtype = c.in_dtype ? c.in_dtype - 1 : SK_BF16;
+    if (!dtype_in_ok(in_dtype)) return SK_ERR_INVALID_ARG;
+    const int out_dtype = c.out_dtype ? c.out_dtype - 1 : (in_dtype == SK_FP8_E4M3 ? SK_BF16 : in_dtype);
+    if (!dtype_out_ok(out_dtype)) return SK_ERR_INVALID_ARG;
+    int32_t blk[3] = {c.blk_m, c.blk_n, c.blk_k};
+    if (!blk[0] || !blk[1] || !blk[2]) {
+        int32_t def[3];
+        sk_default_tile(M, N, K, in_dtype, def);
+        for (int i = 0; i < 3; i++) if (!blk[i]) blk[i] = def[i];
+    }
+    const int grid = c.grid ? c.grid : 256;
+
+    sk_plan_header h{};
+    h.M = M; h.N = N; h.K = K; h.policy = policy;
+    h.blk_m = blk[0]; h.blk_n = blk[1]; h.blk_k = blk[2]; h.grid = grid;
+    h.in_dtype = in_dtype; h.out_dtype = out_dtype;
+    // Algorithm 1, lines 2-3
+    const int64_t tiles_m = ceil_div(M, blk[0]), tiles_n = ceil_div(N, blk[1]);
+    const int64_t ipt = ceil_div(K, blk[2]);
+    const int64_t tiles = tiles_m * tiles_n;
+    const int64_t imax = std::numeric_limits<int32_t>::max();
+    if (tiles_m > imax || tiles_n > imax || tiles > imax - grid || ipt > imax) return SK_ERR_INVALID_ARG;
+    if (tiles > std::numeric_limits<int64_t>::max() / ipt) return SK_ERR_INVALID_ARG;
+    h.tiles_m = (int32_t)tiles_m; h.tiles_n = (int32_t)tiles_n; h.tiles = (int32_t)tiles;
+    h.iters_per_tile = (int32_t)ipt;
+    h.total_iters = tiles * ipt;
+    // Stream-K / data-parallel split (Sec. 3.2, Sec. 4.1)
+    const int b = batches_of(policy);
+    int64_t sk_tiles;
+    if (b < 0) sk_tiles = tiles;
+    else if (b == 0) sk_tiles = 0;
+    else {
+        sk_tiles = tiles % grid + (int64_t)(b - 1) * grid;
+        if (sk_tiles > tiles) sk_tiles = tiles;
+    }
+    h.sk_tiles = (int32_t)sk_tiles;
+    h.dp_tiles = (int32_t)(tiles - sk_tiles);
+    h.sk_iters = sk_tiles * ipt;
+    const int64_t ipw = ceil_div(h.sk_iters, grid);   // Algorithm 1, line 4, on the split region
+    if (ipw > imax) return SK_ERR_INVALID_ARG;
+    h.iters_per_wg = (int32_t)ipw;
+    h.dp_waves = (int32_t)ceil_div(h.dp_tiles, grid);
+    h.has_kernel = sk_kernel_available(in_dtype, blk[0], blk[1], blk[2]) ? 1 : 0;
+
+    sk_plan_t* p = new (std::nothrow) sk_plan_t;
+    if (!p) return SK_ERR_NOMEM;
+    p->h = h;
+    // a tile is split iff some workgroup range ends strictly inside it
+    p->needs_fixup = (h.sk_iters > ipw && ipw % ipt != 0) ? 1 : 0;
+    *out = p;
+    return SK_OK;
+}
+
+extern "C" int sk_plan_info(const sk_plan_t* plan, sk_plan_header* out) {
+    if (!plan || !out) return SK_ERR_INVALID_ARG;
+    *out = plan->h;
+    return SK_OK;
+}
+
+extern "C" int sk_plan_ranges(const sk_plan_t* plan, sk_wg_range* out) {
+    if (!plan || !out) return SK_ERR_INVALID_ARG;
+    for (int x = 0; x < plan->h.grid; x++) expand_wg(plan->h, x, nullptr, &out[x]);
+    return SK_OK;
+}
+
+extern "C" int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t cap, size_t* n) {
+    if (!plan || !n || (!out && cap)) return SK_ERR_INVALID_ARG;
+    std::vector<sk_segment> segs;
+    try {
+        for (int x = 0; x < plan->h.grid; x++) expand_wg(plan->h, x, &segs, nullptr);
+    } catch (const std::bad_alloc&) {
+        return SK_ERR_NOMEM;
+    }
+    *n = segs.size();
+    if (segs.size() > cap) return SK_ERR_INVALID_ARG;
+    if (!segs.empty()) std::memcpy(out, segs.data(), segs.size() * sizeof(sk_segment));
+    return SK_OK;
+}
+
+extern "C" size_t sk_workspace_bytes(const sk_plan_t* plan) {
+    if (!plan) return 0;
+    const sk_plan_header& h = plan->h;
+    return sk_ws_partials_offset(h.grid) + (size_t)h.grid * h.blk_m * h.blk_n * sizeof(float);
+}
+
+extern "C" int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls) {
+    if (!plan) return SK_ERR_INVALID_ARG;
+    plan->spin_limit = polls;
+    return SK_OK;
+}
+
+extern "C" void sk_plan_destroy(sk_plan_t* plan) { delete plan; }
+
+extern "C" const char* sk_status_str(int status) {
+    switch (status) {
+    case SK_OK: return "ok";
+    case SK_ERR_INVALID_ARG: return "invalid argument";
+    case SK_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SK_ERR_WORKSPACE: return "workspace missing or too small";
+    case SK_ERR_HIP: return "HIP runtime error";
+    case SK_ERR_NOMEM: return "out of host memory";
+    case SK_ERR_TIMEOUT: return "tile owner timed out waiting for a partial tile";
+    default: return "unknown status";
+    }
+}

@@ -1,0 +1,145 @@
+"""Parity of the HIP Stream-K GEMM (through the C ABI) with the CPU oracle, on a real MI355X.
+
+Tolerances (the benchmark spec): max relative error <= 1e-2 with fp16 / bf16 output and
+<= 1e-4 on the fp32-accumulator output, with err = max |d - ref| / max(|ref|, rms(ref)).
+Integer-valued inputs are exact in fp32 under every schedule, so they are compared bit-exactly.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_11417_amd as sk
+from paper_2408_11417_amd import inputs
+from oracle import gemm as G
+from oracle import schedule as S
+from tests.gpu_util import Runner, to_device
+
+pytestmark = pytest.mark.gpu
+TOL_16, TOL_32 = 1e-2, 1e-4
+ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16}
+
+
+def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False):
+    M, K = A.shape
+    N = B.shape[1]
+    print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s" %
+          (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype), flush=True)
+    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype)
+    try:
+        # the library's schedule for this very launch equals the oracle's
+        o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"])
+        assert sk.sk_plan_segments(r.plan) == [tuple(s) for s in o.segments]
+        r.run(to_device(A), to_device(B))
+        assert r.check() == sk.SK_OK
+        d = r.result()
+    finally:
+        r.close()
+    if ref is None:
+        ref = G.gemm_fp64(A, B, ODT[dtype], rows=rows)
+    if rows is not None:
+        d = d[rows]
+    if exact:
+        assert np.array_equal(d, ref)
+        return 0.0
+    err = G.rel_error(d, ref)
+    tol = TOL_32 if out_dtype == sk.SK_F32 else TOL_16
+    assert err <= tol, "rel err %.3e > %.1e" % (err, tol)
+    return err
+
+
+@pytest.mark.parametrize("policy", range(8))
+def test_config1_fp16_512_all_policies(policy):
+    c = inputs.config1()
+    ref = G.gemm_fp64(c["A"], c["B"], G.F16)
+    _run_and_compare(c["A"], c["B"], inputs.F16, policy, c["blk"], c["grid"], ref=ref)
+    _run_and_compare(c["A"], c["B"], inputs.F16, policy, c["blk"], c["grid"], out_dtype=sk.SK_F32, ref=ref)
+
+
+TILES = [(128, 128, 32, 4), (128, 128, 64, 4), (256, 128, 64, 4), (256, 256, 64, 8), (64, 128, 64, 4),
+         (32, 128, 64, 4), (16, 128, 64, 4)]
+
+
+@pytest.mark.parametrize("dtype", [inputs.BF16, inputs.F16])
+@pytest.mark.parametrize("blk", [t[:3] for t in TILES])
+def test_integer_inputs_bit_exact_every_tile_and_policy(blk, dtype):
+    # several tiles in each direction plus a ragged tail; grid 24 so that tiles are split unevenly
+    M, N, K = 2 * blk[0] + 40, 3 * blk[1] + 72, 5 * blk[2] + 24
+    A, B = inputs.small_int_pair(M, N, K, dtype, 21)
+    ref = G.gemm_fp64(A, B, ODT[dtype])
+    for policy in range(8):
+        _run_and_compare(A, B, dtype, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True)
+
+
+@pytest.mark.parametrize("shape", [(77, 101, 203), (1, 64, 16), (5, 7, 3), (130, 129, 1), (300, 8, 2049), (16, 264, 520)])
+def test_ragged_and_unaligned_shapes(shape):
+    M, N, K = shape
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 22)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for blk in [(128, 128, 32), (16, 128, 64), (64, 128, 64)]:
+        for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+            _run_and_compare(A, B, inputs.BF16, policy, blk, grid=16, out_dtype=sk.SK_F32, ref=ref, exact=True)
+    A, B = inputs.uniform_pair(M, N, K, inputs.F16, 23)
+    _run_and_compare(A, B, inputs.F16, sk.SK_POLICY_ALL_SK, (128, 128, 32), grid=256)
+
+
+def test_bit_identical_run_to_run_and_flag_reuse():
+    c = inputs.config1()
+    dA, dB = to_device(c["A"]), to_device(c["B"])
+    r = Runner(512, 512, 512, sk.SK_POLICY_ALL_SK, c["blk"], 256, inputs.F16, sk.SK_F32)
+    first = r.run(dA, dB).clone()
+    for i in range(30):                      # same workspace and flags, back to back on one stream
+        D = r.run(dA, dB)
+        if i % 10 == 9:
+            assert torch.equal(D, first)
+    assert r.check() == sk.SK_OK
+    # another plan sharing nothing but the stream, interleaved
+    r2 = Runner(512, 512, 512, sk.SK_POLICY_SK2_DP, (128, 128, 64), 256, inputs.F16, sk.SK_F32)
+    for _ in range(5):
+        r2.run(dA, dB)
+        assert torch.equal(r.run(dA, dB), first)
+    ref = G.gemm_fp64(c["A"], c["B"], G.F16)
+    assert G.rel_error(r2.result(), ref) <= TOL_32
+    r.close()
+    r2.close()
+
+
+def test_owner_timeout_is_reported_and_every_wave_exits():
+    c = inputs.config1()
+    dA, dB = to_device(c["A"]), to_device(c["B"])
+    r = Runner(512, 512, 512, sk.SK_POLICY_ALL_SK, c["blk"], 256, inputs.F16, sk.SK_F32)
+    sk.sk_plan_set_spin_limit(r.plan, 0)     # owners give up at the first unsuccessful poll
+    r.run(dA, dB)
+    st = r.check()                           # the launch must come back either way
+    assert st in (sk.SK_OK, sk.SK_ERR_TIMEOUT)
+    ref = G.gemm_fp64(c["A"], c["B"], G.F16)
+    if st == sk.SK_OK:
+        assert G.rel_error(r.result(), ref) <= TOL_32
+    sk.sk_plan_set_spin_limit(r.plan, 1 << 24)
+    r.run(dA, dB)
+    assert r.check() == sk.SK_OK             # status word was cleared by the previous check
+    assert G.rel_error(r.result(), ref) <= TOL_32
+    r.close()
+
+
+@pytest.mark.parametrize("policy", range(7))
+def test_config2_wave_quantisation_sampled_rows(policy):
+    c = inputs.config2()
+    rows = inputs.sample_rows(c["M"], 48, 100 + policy)
+    _run_and_compare(c["A"], c["B"], inputs.BF16, policy, c["blk"], 256, rows=rows)
+
+
+@pytest.mark.parametrize("M", [16, 32, 64, 128])
+def test_config3_skinny(M):
+    c = inputs.config3(M)
+    ref = G.gemm_fp64(c["A"], c["B"], G.BF16)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(c["A"], c["B"], inputs.BF16, policy, None, 256, ref=ref)
+    _run_and_compare(c["A"], c["B"], inputs.BF16, sk.SK_POLICY_ALL_SK, None, 256, out_dtype=sk.SK_F32, ref=ref)
+
+
+def test_config5_large_square_bf16_sampled_rows():
+    c = inputs.config5(inputs.BF16)
+    rows = inputs.sample_rows(c["M"], 24, 5)
+    ref = G.gemm_fp64(c["A"], c["B"], G.BF16, rows=rows)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK3_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(c["A"], c["B"], inputs.BF16, policy, None, 256, rows=rows, ref=ref)

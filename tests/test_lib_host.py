@@ -1,0 +1,148 @@
+"""Host side of libstreamk.so against the oracles, bit for bit: schedules, Bloom bits, hash;
+plus the ABI surface (every declared symbol exported) and the error paths.  No GPU needed."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import paper_2408_11417_amd as sk
+from oracle import schedule as S
+from oracle import bloom as Bm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "streamk.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b((?:sk|bloom)_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(sk.binding.EXPORTS)
+    lib = ctypes.CDLL(sk.binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def _plan_pair(M, N, K, policy, blk, g):
+    p = sk.sk_plan(M, N, K, policy, blk, g)
+    try:
+        return sk.sk_plan_info(p), sk.sk_plan_ranges(p), sk.sk_plan_segments(p), S.plan(M, N, K, policy, *blk, g)
+    finally:
+        sk.sk_plan_destroy(p)
+
+
+def _assert_same(info, ranges, segs, o):
+    for key in ("tiles_m", "tiles_n", "tiles", "iters_per_tile", "total_iters", "sk_tiles", "dp_tiles",
+                "sk_iters", "iters_per_wg", "dp_waves", "grid", "blk_m", "blk_n", "blk_k", "policy"):
+        assert info[key] == o.header[key], key
+    assert ranges == [tuple(r) for r in o.ranges]
+    assert segs == [tuple(s) for s in o.segments]
+
+
+@settings(max_examples=400, deadline=None)
+@given(st.tuples(st.integers(1, 3000), st.integers(1, 3000), st.integers(1, 5000)),
+       st.tuples(st.sampled_from([16, 32, 64, 128, 256]), st.sampled_from([16, 64, 128, 256]),
+                 st.sampled_from([8, 32, 64, 128])),
+       st.sampled_from([1, 2, 3, 7, 8, 64, 104, 256, 304]), st.integers(0, 7))
+def test_schedule_bit_exact_random(shape, blk, g, policy):
+    _assert_same(*_plan_pair(*shape, policy, blk, g))
+
+
+@pytest.mark.parametrize("policy", range(8))
+@pytest.mark.parametrize("shape,blk", [((512, 512, 512), (128, 128, 32)),
+                                       ((3840, 4224, 4096), (256, 128, 32)),
+                                       ((3840, 4224, 4096), (256, 128, 64)),
+                                       ((16, 8192, 8192), (16, 128, 64)),
+                                       ((128, 8192, 8192), (128, 128, 64)),
+                                       ((8192, 8192, 8192), (256, 256, 64)),
+                                       ((1, 64, 65536), (16, 128, 64)),
+                                       ((16384, 16384, 16384), (256, 256, 64))])
+def test_schedule_bit_exact_benchmark_configs(shape, blk, policy):
+    _assert_same(*_plan_pair(*shape, policy, blk, 256))
+
+
+def test_plan_defaults_and_errors():
+    p = sk.sk_plan(8192, 8192, 8192, sk.SK_POLICY_DP)
+    info = sk.sk_plan_info(p)
+    assert (info["grid"], info["in_dtype"], info["out_dtype"]) == (256, sk.SK_BF16, sk.SK_BF16)
+    assert (info["blk_m"], info["blk_n"], info["blk_k"]) == sk.sk_default_tile(8192, 8192, 8192)
+    assert info["has_kernel"] == 1
+    assert sk.sk_workspace_bytes(p) >= 256 * info["blk_m"] * info["blk_n"] * 4
+    sk.sk_plan_destroy(p)
+    p = sk.sk_plan(64, 64, 64, 0, in_dtype=sk.SK_FP8_E4M3)
+    assert sk.sk_plan_info(p)["out_dtype"] == sk.SK_BF16
+    sk.sk_plan_destroy(p)
+    for bad in [dict(M=0), dict(policy=8), dict(policy=-1), dict(in_dtype=sk.SK_F32), dict(out_dtype=sk.SK_FP8_E4M3),
+                dict(blk=(-1, 16, 16)), dict(grid=-2)]:
+        args = dict(M=64, N=64, K=64, policy=0)
+        args.update(bad)
+        with pytest.raises(sk.StreamKError) as e:
+            sk.sk_plan(**args)
+        assert e.value.status == sk.SK_ERR_INVALID_ARG
+    assert sk.sk_workspace_bytes(None) == 0
+    assert sk.sk_status_str(sk.SK_ERR_WORKSPACE).startswith("workspace")
+
+
+def test_gemm_rejects_bad_arguments_without_touching_the_gpu():
+    p = sk.sk_plan(512, 512, 512, sk.SK_POLICY_ALL_SK, (128, 128, 32))
+    assert sk.sk_gemm_status(0, 256, 512, p) == sk.SK_ERR_INVALID_ARG
+    assert sk.sk_gemm_status(256, 512, 768, None) == sk.SK_ERR_INVALID_ARG
+    assert sk.sk_gemm_status(256, 520, 768, p) == sk.SK_ERR_INVALID_ARG          # misaligned B
+    assert sk.sk_gemm_status(256, 512, 768, p) == sk.SK_ERR_WORKSPACE            # split tiles, no workspace
+    sk.sk_plan_destroy(p)
+    p = sk.sk_plan(512, 512, 512, sk.SK_POLICY_DP, (48, 48, 16))
+    assert sk.sk_plan_info(p)["has_kernel"] == 0
+    assert sk.sk_gemm_status(256, 512, 768, p) == sk.SK_ERR_UNSUPPORTED
+    sk.sk_plan_destroy(p)
+
+
+# ---- Bloom -----------------------------------------------------------------------------------
+
+def test_hash_bit_exact_with_oracle():
+    rng = random.Random(5)
+    for _ in range(3000):
+        key = bytes(rng.getrandbits(8) for _ in range(rng.randint(0, 33)))
+        seed = rng.getrandbits(32)
+        assert sk.bloom_murmur3_32(key, seed) == Bm.murmur3_32(key, seed)
+
+
+def _records(n, seed):
+    rng = random.Random(seed)
+    return [(16 * rng.randint(1, 1024), 16 * rng.randint(1, 1024), 16 * rng.randint(1, 4096), rng.randint(0, 127))
+            for _ in range(n)]
+
+
+@pytest.mark.parametrize("params", [(0, 0, 0), (1024, 3, 7), (64, 1, 2), (95872, 7, 7)])
+def test_bloom_bits_and_queries_bit_exact_with_oracle(params):
+    recs = _records(923, 7)
+    b = sk.bloom_build(recs, *params)
+    o = Bm.build(recs, *(p or d for p, d in zip(params, (Bm.M_BITS, Bm.K_PROBES, Bm.N_FILTERS))))
+    for f in range(o.n_filters):
+        assert sk.bloom_bits(b, f) == o.words[f]
+    rng = random.Random(8)
+    probes = [r[:3] for r in recs[:200]] + [(rng.randint(1, 70000), rng.randint(1, 70000), rng.randint(1, 70000)) for _ in range(800)]
+    for M, N, K in probes:
+        assert sk.bloom_query(b, M, N, K) == o.query(M, N, K)
+    for M, N, K, mask in recs:                                   # no false negatives
+        assert sk.bloom_query(b, M, N, K) & mask == mask & ((1 << o.n_filters) - 1)
+    sk.bloom_destroy(b)
+
+
+def test_bloom_insert_after_build_and_errors():
+    b = sk.bloom_build([])
+    assert sk.bloom_query(b, 512, 512, 512) == 0
+    sk.bloom_insert(b, 512, 512, 512, 0b1000001)
+    assert sk.bloom_query(b, 512, 512, 512) == 0b1000001
+    o = Bm.build([(512, 512, 512, 0b1000001)])
+    assert all(sk.bloom_bits(b, f) == o.words[f] for f in range(7))
+    with pytest.raises(sk.StreamKError):
+        sk.bloom_query(b, -1, 2, 3)
+    with pytest.raises(sk.StreamKError):
+        sk.bloom_query(b, 2 ** 32, 2, 3)
+    with pytest.raises(sk.StreamKError):
+        sk.bloom_bits(b, 7)
+    sk.bloom_destroy(b)
+    with pytest.raises(sk.StreamKError):
+        sk.bloom_build([], 100, 7, 7)                             # not a multiple of 64
