@@ -67,14 +67,25 @@ typedef enum {
     SK_ROLE_CONTRIB = 2  /* starts after K-iteration 0: stores an fp32 partial tile and signals */
 } sk_role;
 
+/* How a tile index maps to a position in the tile grid.  The schedule (which
+ * workgroup runs which tile index) does not depend on it.  GROUPED follows the
+ * remark of Sec. 5.3 that work should be handed out with cache locality in
+ * mind: the grid is cut into bands of 8 tile rows; inside a band the index
+ * walks down the band's rows, then one column to the right, so consecutive
+ * indices (which run at the same time on neighbouring workgroups) share A
+ * row-blocks and B column-blocks. */
+typedef enum { SK_ORDER_ROW_MAJOR = 0, SK_ORDER_GROUPED = 1 } sk_tile_order;
+
 /* Tile shape, grid and types.  A zero field means "library default": the tile
  * is then chosen from (M, N, K), grid = 256 (one workgroup per compute unit),
- * in_dtype = SK_BF16, out_dtype = in_dtype (SK_BF16 for fp8 inputs). */
+ * in_dtype = SK_BF16, out_dtype = in_dtype (SK_BF16 for fp8 inputs),
+ * tile_order = SK_ORDER_GROUPED. */
 typedef struct {
     int32_t blk_m, blk_n, blk_k;
     int32_t grid;
-    int32_t in_dtype;   /* sk_dtype + 1, or 0 for default */
-    int32_t out_dtype;  /* sk_dtype + 1, or 0 for default */
+    int32_t in_dtype;    /* sk_dtype + 1, or 0 for default */
+    int32_t out_dtype;   /* sk_dtype + 1, or 0 for default */
+    int32_t tile_order;  /* sk_tile_order + 1, or 0 for default */
 } sk_config;
 
 /* Numbers of Algorithm 1, lines 2-4, and of the Stream-K / data-parallel split. */
@@ -91,6 +102,7 @@ typedef struct {
     int32_t iters_per_wg;                 /* ceil(sk_iters / grid)                          */
     int32_t dp_waves;                     /* ceil(dp_tiles / grid)                          */
     int32_t has_kernel;                   /* 1 if sk_gemm has a kernel for this tile + dtype */
+    int32_t tile_order;                   /* sk_tile_order                                   */
 } sk_plan_header;
 
 /* Work of one workgroup x: global Stream-K iterations [sk_iter_begin, sk_iter_end)
@@ -102,8 +114,8 @@ typedef struct {
 } sk_wg_range;
 
 /* One MAC-loop call (Algorithm 1, lines 8-13): workgroup wg runs K-iterations
- * [k_begin, k_end) of tile `tile`.  Tile t covers rows (t / tiles_n) * blk_m ...
- * and columns (t % tiles_n) * blk_n ... of D. */
+ * [k_begin, k_end) of tile `tile`.  With (tile_m, tile_n) = sk_plan_tile_coords
+ * the tile covers rows tile_m * blk_m ... and columns tile_n * blk_n ... of D. */
 typedef struct {
     int32_t wg, tile, k_begin, k_end, role;
 } sk_segment;
@@ -130,6 +142,10 @@ int sk_plan_ranges(const sk_plan_t* plan, sk_wg_range* out);
  * *n receives the number of segments; INVALID_ARG if cap is too small (then *n
  * still receives the needed count). */
 int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t cap, size_t* n);
+
+/* Position of a tile index in the tile grid under the plan's tile order.
+ * INVALID_ARG if tile is outside [0, tiles). */
+int sk_plan_tile_coords(const sk_plan_t* plan, int32_t tile, int32_t* tile_m, int32_t* tile_n);
 
 /* Device bytes sk_gemm needs for this plan: one flag line per workgroup, a
  * status word, and one fp32 partial tile (blk_m * blk_n) per workgroup.

@@ -31,7 +31,13 @@ R3  The Stream-K tiles are the lowest tile indices [0, sk_tiles); the
 R4  Algorithm 1 does not clamp a workgroup's range to the iteration total; both
     ends are clamped here (trailing workgroups may be empty).  The split is the
     paper's ceil split, not a balanced one.
-R5  Tile index -> coordinates is row-major over the tile grid.
+R5  Tile index -> coordinates: row-major over the tile grid (order 0), or - because
+    Sec. 5.3 asks for cache locality when work is handed to compute units - grouped
+    (order 1): the grid is cut into bands of 8 tile rows, and inside a band the
+    index walks down the band's rows first and then moves one column to the right,
+    so that consecutive tile indices form compact blocks that share A row-blocks
+    and B column-blocks.  Either order is a bijection; the schedule (which
+    workgroup runs which tile index) is the same for both.
 R6  The workgroup whose segment holds a tile's k-iteration 0 owns the tile; the
     others store an fp32 partial in workspace slot = their workgroup id and the
     owner adds them in ascending workgroup order (= ascending k).
@@ -44,6 +50,8 @@ POLICY_SK4_DP, POLICY_SK5_DP, POLICY_ALL_SK, POLICY_SK6_DP_EXT = 4, 5, 6, 7
 SEVEN_POLICIES = (0, 1, 2, 3, 4, 5, 6)
 
 ROLE_FULL, ROLE_OWNER, ROLE_CONTRIB = 0, 1, 2
+ORDER_ROW_MAJOR, ORDER_GROUPED = 0, 1
+GROUP_ROWS = 8
 
 Segment = namedtuple("Segment", "wg tile k_begin k_end role")
 WgRange = namedtuple("WgRange", "sk_iter_begin sk_iter_end dp_tile_first dp_tile_count")
@@ -85,9 +93,17 @@ def sk_tile_count(tiles, g, policy):
     return min(tiles, rem + (b - 1) * g)
 
 
-def tile_coords(tile, tiles_n):
-    """Row-major tile index -> (tile_m, tile_n) (reading R5)."""
-    return tile // tiles_n, tile % tiles_n
+def tile_coords(tile, tiles_m, tiles_n, order=ORDER_ROW_MAJOR):
+    """Tile index -> (tile_m, tile_n) (reading R5)."""
+    if order == ORDER_ROW_MAJOR:
+        return tile // tiles_n, tile % tiles_n
+    if order != ORDER_GROUPED:
+        raise ValueError("unknown tile order %r" % (order,))
+    per_band = GROUP_ROWS * tiles_n
+    first_row = (tile // per_band) * GROUP_ROWS
+    rows = min(GROUP_ROWS, tiles_m - first_row)       # the last band may be shorter
+    within = tile % per_band
+    return first_row + within % rows, within // rows
 
 
 def wg_sk_range(x, sk_iters, iters_per_wg):
@@ -118,7 +134,7 @@ def wg_sk_segments(x, begin, end, iters_per_tile):
     return segs
 
 
-def plan(M, N, K, policy, blk_m, blk_n, blk_k, g):
+def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR):
     """Full schedule for one problem: header, per-workgroup ranges, canonical segment list.
 
     The segment list is ordered by workgroup, and inside a workgroup in execution
@@ -127,6 +143,8 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g):
     """
     if min(M, N, K, blk_m, blk_n, blk_k, g) < 1:
         raise ValueError("sizes must be positive")
+    if order not in (ORDER_ROW_MAJOR, ORDER_GROUPED):
+        raise ValueError("unknown tile order %r" % (order,))
     tiles_m, tiles_n, tiles, ipt, total = decompose(M, N, K, blk_m, blk_n, blk_k)
     sk_tiles = sk_tile_count(tiles, g, policy)
     dp_tiles = tiles - sk_tiles
@@ -145,7 +163,7 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g):
     header = dict(M=M, N=N, K=K, policy=policy, blk_m=blk_m, blk_n=blk_n, blk_k=blk_k, grid=g,
                   tiles_m=tiles_m, tiles_n=tiles_n, tiles=tiles, iters_per_tile=ipt,
                   total_iters=total, sk_tiles=sk_tiles, dp_tiles=dp_tiles, sk_iters=sk_iters,
-                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g))
+                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g), tile_order=order)
     return Plan(header, ranges, segments)
 
 

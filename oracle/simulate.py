@@ -28,7 +28,7 @@ def run_plan(p, A, B):
     workspace = {}
 
     def mac_loop(seg):
-        tm, tn = S.tile_coords(seg.tile, h["tiles_n"])
+        tm, tn = S.tile_coords(seg.tile, h["tiles_m"], h["tiles_n"], h["tile_order"])
         r0, r1 = tm * bm, min((tm + 1) * bm, M)
         c0, c1 = tn * bn, min((tn + 1) * bn, N)
         acc = np.zeros((r1 - r0, c1 - c0), dtype=np.float32)

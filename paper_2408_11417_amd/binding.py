@@ -8,7 +8,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libstreamk.so")
+LIB_PATH = os.environ.get("STREAMK_LIB") or os.path.join(_HERE, "libstreamk.so")   # override: tuning builds
 if not os.path.exists(LIB_PATH):
     raise ImportError("libstreamk.so is not built: run `python -m paper_2408_11417_amd.build`")
 _lib = ctypes.CDLL(LIB_PATH)
@@ -21,15 +21,16 @@ POLICY_NAMES = ("DP", "SK1_DP", "SK2_DP", "SK3_DP", "SK4_DP", "SK5_DP", "ALL_SK"
 SK_NUM_POLICIES = 7
 SK_F16, SK_BF16, SK_FP8_E4M3, SK_F32 = 0, 1, 2, 3
 SK_ROLE_FULL, SK_ROLE_OWNER, SK_ROLE_CONTRIB = 0, 1, 2
+SK_ORDER_ROW_MAJOR, SK_ORDER_GROUPED = 0, 1
 
-EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_workspace_bytes",
+EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
            "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
            "sk_plan_destroy", "sk_default_tile", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_bits", "bloom_murmur3_32", "bloom_destroy", "sk_status_str")
 
 
 class sk_config(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("blk_m", "blk_n", "blk_k", "grid", "in_dtype", "out_dtype")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("blk_m", "blk_n", "blk_k", "grid", "in_dtype", "out_dtype", "tile_order")]
 
 
 class sk_plan_header(ctypes.Structure):
@@ -40,7 +41,7 @@ class sk_plan_header(ctypes.Structure):
                 ("tiles", ctypes.c_int32), ("iters_per_tile", ctypes.c_int32),
                 ("total_iters", ctypes.c_int64), ("sk_tiles", ctypes.c_int32), ("dp_tiles", ctypes.c_int32),
                 ("sk_iters", ctypes.c_int64), ("iters_per_wg", ctypes.c_int32), ("dp_waves", ctypes.c_int32),
-                ("has_kernel", ctypes.c_int32)]
+                ("has_kernel", ctypes.c_int32), ("tile_order", ctypes.c_int32)]
 
 
 class sk_wg_range(ctypes.Structure):
@@ -65,6 +66,7 @@ _lib.sk_plan.argtypes = [_i64, _i64, _i64, _int, ctypes.POINTER(sk_config), ctyp
 _lib.sk_plan_info.argtypes = [_vp, ctypes.POINTER(sk_plan_header)]
 _lib.sk_plan_ranges.argtypes = [_vp, ctypes.POINTER(sk_wg_range)]
 _lib.sk_plan_segments.argtypes = [_vp, ctypes.POINTER(sk_segment), ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+_lib.sk_plan_tile_coords.argtypes = [_vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
 _lib.sk_workspace_bytes.argtypes = [_vp]
 _lib.sk_workspace_bytes.restype = ctypes.c_size_t
 _lib.sk_plan_set_workspace.argtypes = [_vp, _vp, ctypes.c_size_t]
@@ -107,10 +109,10 @@ def sk_default_tile(M, N, K, in_dtype=SK_BF16):
     return tuple(blk)
 
 
-def sk_plan(M, N, K, policy, blk=None, grid=0, in_dtype=None, out_dtype=None):
+def sk_plan(M, N, K, policy, blk=None, grid=0, in_dtype=None, out_dtype=None, tile_order=None):
     """Returns an opaque plan handle (int).  blk = (blk_m, blk_n, blk_k) or None for the default."""
     cfg = sk_config(*(blk or (0, 0, 0)), grid, 0 if in_dtype is None else in_dtype + 1,
-                    0 if out_dtype is None else out_dtype + 1)
+                    0 if out_dtype is None else out_dtype + 1, 0 if tile_order is None else tile_order + 1)
     out = _vp()
     _check(_lib.sk_plan(M, N, K, policy, ctypes.byref(cfg), ctypes.byref(out)), "sk_plan")
     return out.value
@@ -135,6 +137,12 @@ def sk_plan_segments(plan):
     arr = (sk_segment * max(n.value, 1))()
     _check(_lib.sk_plan_segments(plan, arr, n.value, ctypes.byref(n)), "sk_plan_segments")
     return [(s.wg, s.tile, s.k_begin, s.k_end, s.role) for s in arr[:n.value]]
+
+
+def sk_plan_tile_coords(plan, tile):
+    tm, tn = ctypes.c_int32(), ctypes.c_int32()
+    _check(_lib.sk_plan_tile_coords(plan, tile, ctypes.byref(tm), ctypes.byref(tn)), "sk_plan_tile_coords")
+    return tm.value, tn.value
 
 
 def sk_workspace_bytes(plan):

@@ -5,8 +5,17 @@
 // fp32 partial in the workspace, or - as the tile's owner - waits for the parked
 // partials and adds them in a fixed order (the synchronised reduction that
 // Sec. 5.3 names as the alternative to Algorithm 1's atomic adds).
+//
+// MAC loop data path: A (row-major, k contiguous) and B (row-major, n contiguous)
+// tiles go from global memory straight into LDS with 16-byte LDS-DMA loads, into
+// a ring of NS stages; the LDS image is XOR-swizzled at 16-byte granularity (the
+// swizzle is applied by choosing which global piece each lane fetches) so that
+// the matrix-core operand reads are bank-conflict free without padding.  A
+// operands are read with 16-byte LDS reads, B operands with the transposing
+// 8-byte reads that turn the [k][n] image into k-contiguous lanes.
 #include <hip/hip_runtime.h>
 #include <atomic>
+#include <cstdlib>
 #include <mutex>
 #include "streamk_internal.h"
 
@@ -18,6 +27,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
 struct GemmArgs {
     const void* A;
@@ -27,8 +37,7 @@ struct GemmArgs {
     uint32_t* flags;       // one per workgroup, SK_FLAG_STRIDE bytes apart
     uint32_t* status;      // set non-zero when an owner gives up waiting
     int M, N, K;
-    int tiles_n, tiles, ipt, sk_tiles, ipw, grid;
-    long long sk_iters;
+    int tiles_m, tiles_n, tiles, ipt, sk_tiles, ipw, grid, sk_iters, tile_order;
     uint32_t epoch, spin_limit;
     int out_dtype;
 };
@@ -63,29 +72,85 @@ template <> struct Mfma<SK_F16, 16> {
     }
 };
 
-template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MF_>
+template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MF_, int NSA_, int NSB_ = NSA_>
 struct Cfg {
     static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MF = MF_;
-    static constexpr int THREADS = 64 * WM * WN;
+    static constexpr int NSA = NSA_, NSB = NSB_;        // LDS ring depth of the A and of the B tiles
+    static constexpr int NW = WM * WN, THREADS = 64 * NW;
     static constexpr int WTM = BM / WM, WTN = BN / WN;   // tile of one wave
     static constexpr int MI = WTM / MF, NI = WTN / MF;   // matrix-core blocks per wave tile
     static constexpr int KG = 64 / MF;                   // groups of 8 k across the lanes
     static constexpr int KM = 8 * KG;                    // k per instruction
     static constexpr int KK = BK / KM;
     static constexpr int ACC = MF * MF / 64;             // accumulator registers per block
-    // LDS: A as [BM][BK + 8], B as [BK][BN + 32] 16-bit elements.  The paddings put the 16-byte
-    // reads of 16 consecutive A rows, and the 8-byte transposing reads of 4 consecutive B rows,
-    // on disjoint banks.
-    static constexpr int LDA = BK + 8, LDB = BN + 32;
-    static constexpr int A_ELEMS = BM * LDA, B_ELEMS = BK * LDB;
-    static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
-    static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
-    static constexpr int A_CHUNKS = BM * BK / 8, B_CHUNKS = BK * BN / 8;   // 16-byte pieces per tile
-    static constexpr int CA = (A_CHUNKS + THREADS - 1) / THREADS;
-    static constexpr int CB = (B_CHUNKS + THREADS - 1) / THREADS;
+    // LDS: a ring of NSA A tiles (BM rows of CPA 16-byte pieces) followed by a ring of NSB B tiles
+    // (BK rows of CPB pieces), no padding.  A may be one stage deeper than B: its loads then run
+    // two iterations ahead and only the B tile has to arrive within one iteration.
+    static constexpr int CPA = BK / 8, CPB = BN / 8;
+    static constexpr int A_PIECES = BM * CPA, B_PIECES = BK * CPB;
+    static constexpr int A_BYTES = A_PIECES * 16, B_BYTES = B_PIECES * 16;
+    static constexpr int B_RING = NSA * A_BYTES;         // byte offset of the B ring
+    static constexpr int LDS_BYTES = NSA * A_BYTES + NSB * B_BYTES;
+    // one LDS-DMA instruction of one wave fills 64 consecutive pieces
+    static constexpr bool DIRECT = (A_PIECES % (64 * NW) == 0) && (B_PIECES % (64 * NW) == 0);
+    static constexpr int A_LD = A_PIECES / (64 * NW), B_LD = B_PIECES / (64 * NW);
+    static constexpr int LPS = A_LD + B_LD;              // LDS-DMA loads per stage per wave
+    // register-staged fill (unaligned problems, tiles too small for the DMA split)
+    static constexpr int CA = (A_PIECES + THREADS - 1) / THREADS, CB = (B_PIECES + THREADS - 1) / THREADS;
     static_assert(WTM % MF == 0 && WTN % MF == 0 && BK % KM == 0, "tile does not divide");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(CPA == 4 || CPA == 8 || CPA == 16, "A swizzle assumes 64/128/256-byte rows");
+    static_assert(CPB >= 16, "B swizzle assumes rows of at least 256 bytes");
+    static_assert(NSB >= 2 && (NSA == NSB || NSA == NSB + 1) && LDS_BYTES <= 160 * 1024, "LDS budget / ring depths");
+    static_assert((NSA - 1) * LPS <= 63, "vmcnt range");
+    // LDS-DMA loads that may still be in flight when iteration i starts, if `later` more
+    // iterations follow it.  Issue order inside an iteration: B tile of iteration +NSB-1, then A
+    // tile of iteration +NSA-1; loads complete in order.
+    static constexpr int in_flight(int later) {
+        int n = 0;
+        if (NSA == NSB) {
+            for (int d = 1; d <= NSA - 2; d++) n += later >= d ? LPS : 0;
+        } else {
+            n += later >= 1 ? A_LD : 0;
+            for (int d = 1; d <= NSB - 2; d++) n += (later >= d ? B_LD : 0) + (later >= d + 1 ? A_LD : 0);
+        }
+        return n;
+    }
 };
+
+// ---- LDS image --------------------------------------------------------------------------------
+// A: piece c of row r sits at position c ^ swz_a(r).  Eight consecutive rows and also sixteen
+// consecutive rows then spread the same logical piece over all banks (32- or 64-bank view).
+template <int CPA> __device__ __forceinline__ int swz_a(int r) {
+    if (CPA == 4) return (r >> 1) & 3;
+    return (r & 7) ^ ((r >> 3) & 1);
+}
+// B: piece c of row k sits at position c ^ swz_b(k): rows k..k+3, read together by one transposing
+// read, land on different 32-byte and different 64-byte bank groups.
+__device__ __forceinline__ int swz_b(int k) {
+    const int k0 = k & 1, k1 = (k >> 1) & 1;
+    return (k0 << 1) | (k1 << 2) | (k0 << 3);
+}
+
+// Source of the pieces that lie beyond K in a ragged last k-iteration.
+__device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
+
+// 16 bytes global -> LDS without passing through registers.  The LDS destination of lane l is
+// lds_base + 16 * l; lds_base must be wave-uniform.  Completion is tracked by vmcnt only; the
+// compiler is not told that LDS is written: the caller orders the reads with s_waitcnt + barrier.
+__device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_base) {
+#ifdef SK_EXP_NO_DMA
+    return;
+#endif
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base));
+}
+__device__ __forceinline__ void lds_dma16_ptr(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base));
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N <= 63, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);   // lgkmcnt / expcnt not waited
+}
 
 // Hardware workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous block of
 // logical workgroup ids so that neighbours in the schedule (which share tiles and A row-blocks)
@@ -95,16 +160,17 @@ __device__ __forceinline__ int logical_wg(int hw, int grid) {
 }
 
 template <bool ALIGNED>
-__device__ __forceinline__ uint4 load8(const u16* __restrict__ base, long long row, long long col, int rows, int cols, long long ld) {
-    // 8 consecutive 16-bit elements of a row-major matrix, zero beyond its edges
+__device__ __forceinline__ uint4 load8(const u16* __restrict__ base, int row, int col, int rows, int cols) {
+    // 8 consecutive 16-bit elements of a row-major matrix with `cols` columns, zero beyond its edges
     uint4 v = make_uint4(0, 0, 0, 0);
     if (row < rows) {
+        const u16* p = base + (size_t)((uint32_t)row * (uint32_t)cols + (uint32_t)col);
         if (ALIGNED) {
-            if (col < cols) v = *reinterpret_cast<const uint4*>(base + row * ld + col);
+            if (col < cols) v = *reinterpret_cast<const uint4*>(p);
         } else {
             u16 e[8];
 #pragma unroll
-            for (int i = 0; i < 8; i++) e[i] = (col + i < cols) ? base[row * ld + col + i] : (u16)0;
+            for (int i = 0; i < 8; i++) e[i] = (col + i < cols) ? p[i] : (u16)0;
             v.x = e[0] | (uint32_t)e[1] << 16; v.y = e[2] | (uint32_t)e[3] << 16;
             v.z = e[4] | (uint32_t)e[5] << 16; v.w = e[6] | (uint32_t)e[7] << 16;
         }
@@ -112,77 +178,174 @@ __device__ __forceinline__ uint4 load8(const u16* __restrict__ base, long long r
     return v;
 }
 
+// Register-staged fill of one stage with zero fill at every edge (same LDS image as the DMA path).
 template <class C, bool ALIGNED>
-__device__ __forceinline__ void fetch_tiles(const GemmArgs& g, int m0, int n0, int kit, uint4 (&ra)[C::CA], uint4 (&rb)[C::CB]) {
+__device__ __forceinline__ void fill_stage_staged(const GemmArgs& g, int m0, int n0, int kit, unsigned char* a_stage, unsigned char* b_stage) {
     const int tid = threadIdx.x;
     const u16* A = static_cast<const u16*>(g.A);
     const u16* B = static_cast<const u16*>(g.B);
     const int k0 = kit * C::BK;
+    uint4 ra[C::CA], rb[C::CB];
 #pragma unroll
     for (int i = 0; i < C::CA; i++) {
-        const int c = tid + i * C::THREADS;
-        if (C::A_CHUNKS % C::THREADS == 0 || c < C::A_CHUNKS)
-            ra[i] = load8<ALIGNED>(A, m0 + c / (C::BK / 8), k0 + (c % (C::BK / 8)) * 8, g.M, g.K, g.K);
+        const int p = tid + i * C::THREADS;
+        if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES)
+            ra[i] = load8<ALIGNED>(A, m0 + p / C::CPA, k0 + (p % C::CPA) * 8, g.M, g.K);
     }
 #pragma unroll
     for (int i = 0; i < C::CB; i++) {
-        const int c = tid + i * C::THREADS;
-        if (C::B_CHUNKS % C::THREADS == 0 || c < C::B_CHUNKS)
-            rb[i] = load8<ALIGNED>(B, k0 + c / (C::BN / 8), n0 + (c % (C::BN / 8)) * 8, g.K, g.N, g.N);
+        const int p = tid + i * C::THREADS;
+        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES)
+            rb[i] = load8<ALIGNED>(B, k0 + p / C::CPB, n0 + (p % C::CPB) * 8, g.K, g.N);
     }
-}
-
-template <class C>
-__device__ __forceinline__ void stash_tiles(u16* stage, const uint4 (&ra)[C::CA], const uint4 (&rb)[C::CB]) {
-    const int tid = threadIdx.x;
-    u16* sA = stage;
-    u16* sB = stage + C::A_ELEMS;
+    uint4* sA = reinterpret_cast<uint4*>(a_stage);
+    uint4* sB = reinterpret_cast<uint4*>(b_stage);
 #pragma unroll
     for (int i = 0; i < C::CA; i++) {
-        const int c = tid + i * C::THREADS;
-        if (C::A_CHUNKS % C::THREADS == 0 || c < C::A_CHUNKS)
-            *reinterpret_cast<uint4*>(sA + (c / (C::BK / 8)) * C::LDA + (c % (C::BK / 8)) * 8) = ra[i];
+        const int p = tid + i * C::THREADS, r = p / C::CPA;
+        if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES) sA[r * C::CPA + ((p % C::CPA) ^ swz_a<C::CPA>(r))] = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < C::CB; i++) {
-        const int c = tid + i * C::THREADS;
-        if (C::B_CHUNKS % C::THREADS == 0 || c < C::B_CHUNKS)
-            *reinterpret_cast<uint4*>(sB + (c / (C::BN / 8)) * C::LDB + (c % (C::BN / 8)) * 8) = rb[i];
+        const int p = tid + i * C::THREADS, k = p / C::CPB;
+        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES) sB[k * C::CPB + ((p % C::CPB) ^ swz_b(k))] = rb[i];
     }
 }
 
-// 4 k-consecutive elements of one B column out of the row-major [k][n] LDS tile: the
+// Per-tile addressing of the LDS-DMA loads: lane l of this wave's j-th A instruction fills A
+// position (j * NW + wave) * 64 + l.  Rows beyond M and columns beyond N are clamped to the last
+// valid one: they only feed output elements that are never stored.
+template <class C> struct DmaMap {
+    uint32_t a_off[C::A_LD > 0 ? C::A_LD : 1];   // byte offsets from A / B at k-iteration 0
+    uint32_t b_off[C::B_LD > 0 ? C::B_LD : 1];
+    __device__ __forceinline__ void init(const GemmArgs& g, int m0, int n0) {
+        const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+#pragma unroll
+        for (int j = 0; j < C::A_LD; j++) {
+            const int p = (j * C::NW + wave) * 64 + lane;
+            const int r = p / C::CPA, c = (p % C::CPA) ^ swz_a<C::CPA>(r);
+            int row = m0 + r;
+            row = row < g.M ? row : g.M - 1;
+            a_off[j] = ((uint32_t)row * (uint32_t)g.K + 8u * c) * 2u;
+        }
+#pragma unroll
+        for (int j = 0; j < C::B_LD; j++) {
+            const int p = (j * C::NW + wave) * 64 + lane;
+            const int k = p / C::CPB, c = (p % C::CPB) ^ swz_b(k);
+            int col = n0 + 8 * c;
+            col = col < g.N ? col : g.N - 8;
+            b_off[j] = ((uint32_t)k * (uint32_t)g.N + (uint32_t)col) * 2u;
+        }
+    }
+    // Loads of k-iteration `kit`.  TAIL: the iteration reaches beyond K (K is a multiple of 8
+    // here); pieces at k >= K are then fetched from a zero piece so that they add nothing.
+    template <bool TAIL> __device__ __forceinline__ void issue_a(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::A_LD) const {
+        const int lane = threadIdx.x % 64;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+        const char* A = static_cast<const char*>(g.A) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * 2));
+#pragma unroll
+        for (int j = 0; j < C::A_LD; j++) {
+            if (j < j0 || j >= j1) continue;
+            if (!TAIL) {
+                lds_dma16(A, a_off[j], lds + (j * C::NW + wave) * 1024);
+            } else {
+                const int p = (j * C::NW + wave) * 64 + lane;
+                const int r = p / C::CPA, c = (p % C::CPA) ^ swz_a<C::CPA>(r);
+                const char* src = kit * C::BK + 8 * c < g.K ? A + a_off[j] : reinterpret_cast<const char*>(g_zero_piece);
+                lds_dma16_ptr(src, lds + (j * C::NW + wave) * 1024);
+            }
+        }
+    }
+    template <bool TAIL> __device__ __forceinline__ void issue_b(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::B_LD) const {
+        const int lane = threadIdx.x % 64;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+        const char* B = static_cast<const char*>(g.B) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * 2)) * (uint32_t)g.N;
+#pragma unroll
+        for (int j = 0; j < C::B_LD; j++) {
+            if (j < j0 || j >= j1) continue;
+            if (!TAIL) {
+                lds_dma16(B, b_off[j], lds + (j * C::NW + wave) * 1024);
+            } else {
+                const int p = (j * C::NW + wave) * 64 + lane;
+                const char* src = kit * C::BK + p / C::CPB < g.K ? B + b_off[j] : reinterpret_cast<const char*>(g_zero_piece);
+                lds_dma16_ptr(src, lds + (j * C::NW + wave) * 1024);
+            }
+        }
+    }
+};
+
+// 4 k-consecutive elements of one B column out of the row-major [k][n] LDS image: the
 // transposing read hands lane j of each 16-lane group column j of a 4 x 16 block whose rows are
 // addressed by lanes 4e..4e+3 of the group.
-__device__ __forceinline__ uint2 read_b_transposed(const u16* p) {
+__device__ __forceinline__ uint2 read_b_transposed(const unsigned char* p) {
     s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
     return __builtin_bit_cast(uint2, v);
 }
 
-template <class C>
-__device__ __forceinline__ void mac_stage(const u16* stage, typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
-    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
-    const int wm = wave / C::WN, wn = wave % C::WN;
-    const u16* sA = stage + (wm * C::WTM + lane % C::MF) * C::LDA + 8 * (lane / C::MF);
-    const u16* sB = stage + C::A_ELEMS + (8 * (lane / C::MF) + (lane % 16) / 4) * C::LDB
-                  + wn * C::WTN + 16 * ((lane % C::MF) / 16) + 4 * (lane % 4);
+// Lane-constant parts of the operand addresses inside a stage.
+template <class C> struct FragMap {
+    uint32_t a_kk[C::KK];   // byte offset of this lane's A piece for k-step kk, matrix-core block row 0
+    uint32_t b_ni[C::NI];   // byte offset of this lane's B read for block column ni, k-step 0, half 0
+    __device__ __forceinline__ void init() {
+        const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+        const int wm = wave / C::WN, wn = wave % C::WN;
+        const int row = wm * C::WTM + lane % C::MF;          // + mi * MF keeps row % 16
 #pragma unroll
-    for (int kk = 0; kk < C::KK; kk++) {
-        uint4 af[C::MI], bf[C::NI];
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++)
-            af[mi] = *reinterpret_cast<const uint4*>(sA + mi * C::MF * C::LDA + kk * C::KM);
+        for (int kk = 0; kk < C::KK; kk++)
+            a_kk[kk] = (row * C::CPA + ((kk * C::KG + lane / C::MF) ^ swz_a<C::CPA>(row))) * 16;
+        const int krow = 8 * (lane / C::MF) + (lane % 16) / 4;   // + kk * KM + 4 * half keeps krow % 4
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++) {
-            const u16* p = sB + kk * C::KM * C::LDB + ni * C::MF;
-            const uint2 lo = read_b_transposed(p), hi = read_b_transposed(p + 4 * C::LDB);
-            bf[ni] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            const int col = wn * C::WTN + ni * C::MF + 16 * ((lane % C::MF) / 16) + 4 * (lane % 4);
+            b_ni[ni] = (krow * C::CPB + ((col / 8) ^ swz_b(krow))) * 16 + (col % 8) * 2;
         }
+    }
+};
+
+template <class C> struct Frags {
+    uint4 a[C::MI], b[C::NI];
+    __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; mi++)
+            a[mi] = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk] + mi * C::MF * C::CPA * 16);
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ni++) {
+            const unsigned char* p = b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16;
+            const uint2 lo = read_b_transposed(p), hi = read_b_transposed(p + 4 * C::CPB * 16);
+            b[ni] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+    }
+};
+
+struct NoIssue {
+    __device__ __forceinline__ void operator()(int) const {}
+};
+
+// All k-steps of one stage: the operands of step kk+1 are read from LDS while the matrix cores
+// work on step kk.  issue(kk) is called once per k-step: the caller spreads the global->LDS
+// requests of a later stage over the steps, so that no wave sits in a burst of memory
+// instructions while the matrix cores idle.
+template <class C, class Issue>
+__device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm,
+                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI], const Issue& issue) {
+#ifdef SK_EXP_NO_COMPUTE
+    return;
+#endif
+    Frags<C> f[2];
+    f[0].load(a_stage, b_stage, fm, 0);
+#pragma unroll
+    for (int kk = 0; kk < C::KK; kk++) {
+        if (kk + 1 < C::KK) f[(kk + 1) & 1].load(a_stage, b_stage, fm, kk + 1);
+        issue(kk);
 #pragma unroll
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
             for (int ni = 0; ni < C::NI; ni++)
-                acc[mi][ni] = Mfma<C::DT, C::MF>::run(af[mi], bf[ni], acc[mi][ni]);
+#ifdef SK_EXP_NO_MFMA
+                acc[mi][ni][0] += __uint_as_float(f[kk & 1].a[mi].x ^ f[kk & 1].b[ni].y);
+#else
+                acc[mi][ni] = Mfma<C::DT, C::MF>::run(f[kk & 1].a[mi], f[kk & 1].b[ni], acc[mi][ni]);
+#endif
     }
 }
 
@@ -192,17 +355,153 @@ __device__ __forceinline__ u16 to_bf16_bits(float f) {
     return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);                   // round to nearest even
 }
 
+template <class C, int LATER> __device__ __forceinline__ void wait_stage(int later) {
+    // wait until the loads of the current iteration have landed, given how many iterations follow
+    if (LATER == 0 || later >= LATER) wait_vmcnt<C::in_flight(LATER)>();
+    else wait_stage<C, (LATER > 0 ? LATER - 1 : 0)>(later);
+}
+
+// MAC loop of one segment (Algorithm 1, line 13): k-iterations [k_begin, k_end) of one tile.
+template <class C, bool ALIGNED>
+__device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int k_begin, int k_end,
+                                         unsigned char* smem, const FragMap<C>& fm,
+#ifdef SK_EXP_CLOCK
+                                         unsigned long long (&exp_t)[4],
+#endif
+                                         typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+    const int nk = k_end - k_begin;
+    if (C::DIRECT && ALIGNED) {
+        // A tile of iteration i sits in A ring slot i % NSA, its B tile in B ring slot i % NSB; in
+        // iteration i the B tile of iteration i+NSB-1 and then the A tile of iteration i+NSA-1 are requested
+        const uint32_t lds0 = (uint32_t)(size_t)(lds_byte*)smem;
+        const int full_k = g.K / C::BK;             // iterations below this index are entirely inside K
+        DmaMap<C> dm;
+        dm.init(g, m0, n0);
+#pragma unroll
+        for (int j = 1 - C::NSA; j < 0; j++) {       // the requests that iterations before the first would have made
+            const int ib = j + C::NSB - 1, ia = j + C::NSA - 1;
+            if (ib >= 0 && ib < nk) {
+                if (k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds0 + C::B_RING + ib * C::B_BYTES);
+                else dm.template issue_b<true>(g, k_begin + ib, lds0 + C::B_RING + ib * C::B_BYTES);
+            }
+            if (ia >= 0 && ia < nk) {
+                if (k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds0 + ia * C::A_BYTES);
+                else dm.template issue_a<true>(g, k_begin + ia, lds0 + ia * C::A_BYTES);
+            }
+        }
+        int sa = 0, sb = 0, fa = C::NSA - 1, fb = C::NSB - 1;   // ring slots: current A / B, A / B to refill
+        for (int i = 0; i < nk; i++) {
+#ifdef SK_EXP_CLOCK
+            const unsigned long long t0 = __builtin_readcyclecounter();
+#endif
+            wait_stage<C, C::NSA - 1>(nk - 1 - i);
+#ifdef SK_EXP_CLOCK
+            const unsigned long long t1 = __builtin_readcyclecounter();
+#endif
+            __syncthreads();
+#ifdef SK_EXP_CLOCK
+            const unsigned long long t2 = __builtin_readcyclecounter();
+#endif
+            const int ib = i + C::NSB - 1, ia = i + C::NSA - 1;
+            const bool do_b = ib < nk, do_a = ia < nk;
+            const bool tail_b = k_begin + ib >= full_k, tail_a = k_begin + ia >= full_k;
+            const uint32_t lds_b = lds0 + C::B_RING + fb * C::B_BYTES, lds_a = lds0 + fa * C::A_BYTES;
+            // request q of this iteration: the B_LD loads of the B tile first, then the A_LD loads of the A tile
+            auto issue = [&](int kk) {
+                const int q0 = kk * C::LPS / C::KK, q1 = (kk + 1) * C::LPS / C::KK;
+                const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
+                const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
+                if (do_b && b1 > b0) {
+                    if (!tail_b) dm.template issue_b<false>(g, k_begin + ib, lds_b, b0, b1);
+                    else dm.template issue_b<true>(g, k_begin + ib, lds_b, b0, b1);
+                }
+                if (do_a && a1 > a0) {
+                    if (!tail_a) dm.template issue_a<false>(g, k_begin + ia, lds_a, a0, a1);
+                    else dm.template issue_a<true>(g, k_begin + ia, lds_a, a0, a1);
+                }
+            };
+#ifdef SK_EXP_CLOCK
+            const unsigned long long t3 = __builtin_readcyclecounter();
+#endif
+            mac_stage<C>(smem + sa * C::A_BYTES, smem + C::B_RING + sb * C::B_BYTES, fm, acc, issue);
+#ifdef SK_EXP_CLOCK
+            const unsigned long long t4 = __builtin_readcyclecounter();
+            exp_t[0] += t1 - t0; exp_t[1] += t2 - t1; exp_t[2] += t3 - t2; exp_t[3] += t4 - t3;
+#endif
+            sa = sa + 1 == C::NSA ? 0 : sa + 1;
+            fa = fa + 1 == C::NSA ? 0 : fa + 1;
+            sb = sb + 1 == C::NSB ? 0 : sb + 1;
+            fb = fb + 1 == C::NSB ? 0 : fb + 1;
+        }
+        __syncthreads();                             // all reads done before the next segment refills
+    } else {
+        for (int k = k_begin; k < k_end; k++) {
+            const int slot = (k - k_begin) & 1;
+            unsigned char* a_stage = smem + slot * C::A_BYTES;
+            unsigned char* b_stage = smem + C::B_RING + slot * C::B_BYTES;
+            fill_stage_staged<C, ALIGNED>(g, m0, n0, k, a_stage, b_stage);
+            __syncthreads();
+            mac_stage<C>(a_stage, b_stage, fm, acc, NoIssue());
+        }
+        __syncthreads();
+    }
+}
+
+// Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): per accumulator block, add the
+// parked partials of the contributors in ascending workgroup order (= ascending k), convert and
+// store.  OUT selects the output type, EDGE adds the bounds checks.  Working one block at a time
+// keeps the register need flat.
+template <class C, int OUT, bool EDGE>
+__device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
+                                                 const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+    typedef typename Mfma<C::DT, C::MF>::Acc Acc;
+#pragma unroll
+    for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ni++) {
+            Acc blk = acc[mi][ni];
+            const float* src = part0 + ((mi * C::NI + ni) * C::ACC) * C::THREADS;
+            for (int c = 0; c < n_contrib; c++) {
+                float v[C::ACC];
+#pragma unroll
+                for (int r = 0; r < C::ACC; r++)
+                    v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
+                src += C::BM * C::BN;
+            }
+            const int col = col0 + ni * C::MF;
+#pragma unroll
+            for (int r = 0; r < C::ACC; r++) {
+                const int row = row0 + mi * C::MF + (r / 4) * (4 * C::KG) + r % 4;
+                if (!EDGE || (row < g.M && col < g.N)) {
+                    const size_t o = (size_t)((uint32_t)row * (uint32_t)g.N + (uint32_t)col);
+                    const float v = blk[r];
+                    if (OUT == SK_F32) static_cast<float*>(g.D)[o] = v;
+                    else if (OUT == SK_BF16) static_cast<u16*>(g.D)[o] = to_bf16_bits(v);
+                    else static_cast<_Float16*>(g.D)[o] = (_Float16)v;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+}
+
 template <class C, bool ALIGNED>
 __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    u16* smem = reinterpret_cast<u16*>(smem_raw);
+    extern __shared__ __align__(1024) unsigned char smem[];
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / C::WN, wn = wave % C::WN;
     const int x = logical_wg(blockIdx.x, g.grid);
+    FragMap<C> fm;
+    fm.init();
+#ifdef SK_EXP_CLOCK
+    const unsigned long long exp_c0 = __builtin_readcyclecounter(), exp_r0 = __builtin_amdgcn_s_memrealtime();
+    unsigned long long exp_t[4] = {0, 0, 0, 0};
+#endif
 
     // Algorithm 1, lines 5-6 (clamped): this workgroup's share of the Stream-K iterations
-    long long it = (long long)x * g.ipw, it_end = it + g.ipw;
+    int it = x * g.ipw, it_end = it + g.ipw;
     if (it > g.sk_iters) it = g.sk_iters;
     if (it_end > g.sk_iters) it_end = g.sk_iters;
     int dp_tile = g.sk_tiles + x;   // data-parallel tiles come after the Stream-K work
@@ -210,11 +509,11 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     while (true) {
         int tile, k_begin, k_end;
         if (it < it_end) {                       // Algorithm 1, lines 8-12
-            tile = (int)(it / g.ipt);
-            const long long tile_first = (long long)tile * g.ipt;
-            k_begin = (int)(it - tile_first);
-            const long long stop = it_end < tile_first + g.ipt ? it_end : tile_first + g.ipt;
-            k_end = (int)(stop - tile_first);
+            tile = (int)((uint32_t)it / (uint32_t)g.ipt);
+            const int tile_first = tile * g.ipt;
+            k_begin = it - tile_first;
+            const int stop = it_end < tile_first + g.ipt ? it_end : tile_first + g.ipt;
+            k_end = stop - tile_first;
             it = tile_first + g.ipt;
         } else if (dp_tile < g.tiles) {
             tile = dp_tile; k_begin = 0; k_end = g.ipt;
@@ -222,55 +521,69 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         } else {
             break;
         }
-        const int m0 = (tile / g.tiles_n) * C::BM, n0 = (tile % g.tiles_n) * C::BN;
+        int tm, tn;
+        if (g.tile_order == SK_ORDER_ROW_MAJOR) {
+            tm = (int)((uint32_t)tile / (uint32_t)g.tiles_n);
+            tn = tile - tm * g.tiles_n;
+        } else {                                 // bands of 8 tile rows, walked column by column
+            const uint32_t per_band = (uint32_t)(SK_GROUP_ROWS * g.tiles_n);
+            const uint32_t band = (uint32_t)tile / per_band, within = (uint32_t)tile - band * per_band;
+            const int left = g.tiles_m - (int)band * SK_GROUP_ROWS;
+            const uint32_t rows = (uint32_t)(left < SK_GROUP_ROWS ? left : SK_GROUP_ROWS);
+            tn = (int)(within / rows);
+            tm = (int)band * SK_GROUP_ROWS + (int)(within - (uint32_t)tn * rows);
+        }
+#ifdef SK_EXP_SAME_TILE
+        tm = tn = 0;
+#endif
+        const int m0 = tm * C::BM, n0 = tn * C::BN;
 
-        // ---- MAC loop (Algorithm 1, line 13): global -> registers -> LDS (two stages) -> matrix cores
         Acc acc[C::MI][C::NI];
 #pragma unroll
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
-            for (int ni = 0; ni < C::NI; ni++)
-#pragma unroll
-                for (int r = 0; r < C::ACC; r++) acc[mi][ni][r] = 0.f;
-        {
-            uint4 ra[C::CA], rb[C::CB];
-            fetch_tiles<C, ALIGNED>(g, m0, n0, k_begin, ra, rb);
-            stash_tiles<C>(smem, ra, rb);
-            __syncthreads();
-            for (int k = k_begin; k < k_end; k++) {
-                const int cur = (k - k_begin) & 1;
-                const bool more = k + 1 < k_end;
-                if (more) fetch_tiles<C, ALIGNED>(g, m0, n0, k + 1, ra, rb);
-                mac_stage<C>(smem + cur * C::STAGE_ELEMS, acc);
-                if (more) stash_tiles<C>(smem + (cur ^ 1) * C::STAGE_ELEMS, ra, rb);
-                __syncthreads();
-            }
-        }
+            for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
+#ifdef SK_EXP_CLOCK
+        mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, exp_t, acc);
+#else
+        mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, acc);
+#endif
 
         // ---- fix-up
-        float4* slot = reinterpret_cast<float4*>(g.partials + (size_t)x * C::BM * C::BN);
+        // (the empty asm statements keep the per-block addresses from being computed once, ahead
+        // of the persistent loop, where they would occupy registers for the whole kernel)
         if (k_begin > 0) {
             // contributor: park the accumulators (register order, coalesced), then signal
+            // Partial tiles are stored and loaded with device-scope atomic accesses (one dword
+            // per lane, lanes contiguous): these are coherent across the XCDs' L2 caches by
+            // themselves, so no L2 write-back / invalidate is needed around the exchange.
+            float* slot = g.partials + (size_t)x * (C::BM * C::BN) + tid;
+            asm volatile("" : "+v"(slot));
 #pragma unroll
             for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
-                for (int ni = 0; ni < C::NI; ni++)
+                for (int ni = 0; ni < C::NI; ni++) {
 #pragma unroll
-                    for (int q = 0; q < C::ACC / 4; q++)
-                        slot[((mi * C::NI + ni) * (C::ACC / 4) + q) * C::THREADS + tid] =
-                            make_float4(acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1], acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]);
-            __threadfence();                      // make the partial visible device-wide (all XCDs)
+                    for (int r = 0; r < C::ACC; r++)
+                        __hip_atomic_store(slot + ((mi * C::NI + ni) * C::ACC + r) * C::THREADS, acc[mi][ni][r],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            wait_vmcnt<0>();                      // every lane's part of the partial tile has reached memory
             __syncthreads();
             if (tid == 0)
-                __hip_atomic_store(g.flags + (size_t)x * (SK_FLAG_STRIDE / 4), g.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(g.flags + (size_t)x * (SK_FLAG_STRIDE / 4), g.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             continue;
         }
+        int n_contrib = 0;
         if (k_end < g.ipt) {
-            // owner: contributors are the following workgroups up to the one holding the tile's last iteration
-            const int last = (int)(((long long)tile * g.ipt + g.ipt - 1) / g.ipw);
-            for (int c = x + 1; c <= last; c++) {
-                if (tid == 0) {
-                    uint32_t polls = 0;
+            // owner: contributors are the following workgroups up to the one holding the tile's
+            // last iteration.  Wait for all of them; the epilogue adds their partials in a fixed
+            // order, so the result does not depend on timing.
+            const int last = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
+            if (tid == 0) {
+                uint32_t polls = 0;
+                for (int c = x + 1; c <= last; c++) {
                     while (__hip_atomic_load(g.flags + (size_t)c * (SK_FLAG_STRIDE / 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.epoch) {
                         if (polls++ >= g.spin_limit) {   // bounded wait: record and go on
                             __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -279,71 +592,77 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
                         __builtin_amdgcn_s_sleep(2);
                     }
                 }
-                __syncthreads();
-                __threadfence();                  // acquire: drop stale cached copies of the slot
-                const float4* src = reinterpret_cast<const float4*>(g.partials + (size_t)c * C::BM * C::BN);
-#pragma unroll
-                for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-                    for (int ni = 0; ni < C::NI; ni++)
-#pragma unroll
-                        for (int q = 0; q < C::ACC / 4; q++) {
-                            const float4 v = src[((mi * C::NI + ni) * (C::ACC / 4) + q) * C::THREADS + tid];
-                            acc[mi][ni][4 * q] += v.x; acc[mi][ni][4 * q + 1] += v.y;
-                            acc[mi][ni][4 * q + 2] += v.z; acc[mi][ni][4 * q + 3] += v.w;
-                        }
             }
+            __syncthreads();
+            n_contrib = last - x;
         }
 
         // ---- epilogue: fp32 accumulators -> D
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ni++) {
-                const int col = n0 + wn * C::WTN + ni * C::MF + lane % C::MF;
-#pragma unroll
-                for (int r = 0; r < C::ACC; r++) {
-                    const int row = m0 + wm * C::WTM + mi * C::MF + (r / 4) * (4 * C::KG) + 4 * (lane / C::MF) + r % 4;
-                    if (row < g.M && col < g.N) {
-                        const size_t o = (size_t)row * g.N + col;
-                        const float v = acc[mi][ni][r];
-                        if (g.out_dtype == SK_F32) static_cast<float*>(g.D)[o] = v;
-                        else if (g.out_dtype == SK_BF16) static_cast<u16*>(g.D)[o] = to_bf16_bits(v);
-                        else static_cast<_Float16*>(g.D)[o] = (_Float16)v;
-                    }
-                }
-            }
+        int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
+        asm volatile("" : "+v"(row0), "+v"(col0));
+        const float* part0 = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
+        asm volatile("" : "+v"(part0));
+        const bool edge = m0 + C::BM > g.M || n0 + C::BN > g.N;
+        if (g.out_dtype == SK_BF16) {
+            if (edge) reduce_and_store<C, SK_BF16, true>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_BF16, false>(g, row0, col0, part0, n_contrib, acc);
+        } else if (g.out_dtype == SK_F16) {
+            if (edge) reduce_and_store<C, SK_F16, true>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_F16, false>(g, row0, col0, part0, n_contrib, acc);
+        } else {
+            if (edge) reduce_and_store<C, SK_F32, true>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_F32, false>(g, row0, col0, part0, n_contrib, acc);
+        }
     }
+#ifdef SK_EXP_CLOCK
+    if (x == 0 && tid == 0 && g.status) {
+        unsigned long long* dbg = reinterpret_cast<unsigned long long*>(g.status) + 1;
+        dbg[0] = __builtin_readcyclecounter() - exp_c0;
+        dbg[1] = __builtin_amdgcn_s_memrealtime() - exp_r0;
+    }
+    if (x == 0 && lane == 0 && g.status) {
+        unsigned long long* dbg = reinterpret_cast<unsigned long long*>(g.status) + 3 + wave * 4;
+        for (int q = 0; q < 4; q++) dbg[q] = exp_t[q];
+    }
+#endif
 }
 
 // ---- host side ---------------------------------------------------------------------------------
 typedef void (*kernel_fn)(GemmArgs);
 struct KernelEntry {
-    int dtype, bm, bn, bk;
+    int dtype, bm, bn, bk, variant;
     kernel_fn aligned, generic;
     int threads, lds_bytes;
     std::atomic<int> max_resident{-1};   // co-resident workgroups on the device, -1 = not yet asked
-    KernelEntry(int d, int m, int n, int k, kernel_fn a, kernel_fn g, int t, int l)
-        : dtype(d), bm(m), bn(n), bk(k), aligned(a), generic(g), threads(t), lds_bytes(l) {}
+    KernelEntry(int d, int m, int n, int k, int v, kernel_fn a, kernel_fn g, int t, int l)
+        : dtype(d), bm(m), bn(n), bk(k), variant(v), aligned(a), generic(g), threads(t), lds_bytes(l) {}
 };
 
-template <class C> KernelEntry* make_entry() {
-    return new KernelEntry(C::DT, C::BM, C::BN, C::BK, streamk_gemm_kernel<C, true>, streamk_gemm_kernel<C, false>,
+template <class C> KernelEntry* make_entry(int variant = 0) {
+    return new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, streamk_gemm_kernel<C, true>, streamk_gemm_kernel<C, false>,
                            C::THREADS, C::LDS_BYTES);
 }
 
+// Tile shapes with a kernel: <dtype, BM, BN, BK, waves along M, waves along N, matrix-core block,
+// A ring depth[, B ring depth]>.
+// Variant 0 of a shape is the one sk_gemm uses; other variants are alternative wave layouts of the
+// same shape, selectable with the environment variable SK_KERNEL_VARIANT for tuning runs.
 template <int DT> void add_dtype(KernelEntry** t, int* n) {
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 2, 32>>();
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32>>();
-    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32>>();
-    t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32>>();
-    t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16>>();
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 2, 32, 4>>();
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2>>(1);
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 2, 2>>(2);
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 4, 32, 4>>(1);
+    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>();
+    t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>>();
+    t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>>();
 }
 
 KernelEntry** kernel_table(int* count) {
-    static KernelEntry* table[32];
+    static KernelEntry* table[64];
     static int n = 0;
     static std::once_flag once;
     std::call_once(once, [] {
@@ -357,9 +676,15 @@ KernelEntry** kernel_table(int* count) {
 KernelEntry* find_kernel(int dtype, int bm, int bn, int bk) {
     int n;
     KernelEntry** t = kernel_table(&n);
+    const char* env = getenv("SK_KERNEL_VARIANT");
+    const int want = env ? atoi(env) : 0;
+    KernelEntry* fallback = nullptr;
     for (int i = 0; i < n; i++)
-        if (t[i]->dtype == dtype && t[i]->bm == bm && t[i]->bn == bn && t[i]->bk == bk) return t[i];
-    return nullptr;
+        if (t[i]->dtype == dtype && t[i]->bm == bm && t[i]->bn == bn && t[i]->bk == bk) {
+            if (t[i]->variant == want) return t[i];
+            if (t[i]->variant == 0) fallback = t[i];
+        }
+    return fallback;
 }
 
 std::atomic<uint32_t> g_epoch{0};
@@ -399,7 +724,9 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     const sk_plan_header& h = plan->h;
     const uintptr_t align = reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(D);
     if (align & 15) return SK_ERR_INVALID_ARG;
-    if (h.M > 0x7FFFFFFF || h.N > 0x7FFFFFFF || h.K > 0x7FFFFFFF) return SK_ERR_UNSUPPORTED;
+    // the kernels use 32-bit byte offsets into A and B, 32-bit element offsets into D and 32-bit iteration counts
+    if (h.M * h.K >= (1ll << 31) || h.K * h.N >= (1ll << 31) || h.M * h.N >= (1ll << 32) || h.total_iters >= (1ll << 30))
+        return SK_ERR_UNSUPPORTED;
     KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k);
     if (!e) return SK_ERR_UNSUPPORTED;
     if (plan->needs_fixup && !plan->workspace) return SK_ERR_WORKSPACE;
@@ -428,8 +755,8 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.status = ws ? reinterpret_cast<uint32_t*>(ws + sk_ws_status_offset(h.grid)) : nullptr;
     g.partials = ws ? reinterpret_cast<float*>(ws + sk_ws_partials_offset(h.grid)) : nullptr;
     g.M = (int)h.M; g.N = (int)h.N; g.K = (int)h.K;
-    g.tiles_n = h.tiles_n; g.tiles = h.tiles; g.ipt = h.iters_per_tile;
-    g.sk_tiles = h.sk_tiles; g.ipw = h.iters_per_wg; g.grid = h.grid; g.sk_iters = h.sk_iters;
+    g.tiles_m = h.tiles_m; g.tiles_n = h.tiles_n; g.tiles = h.tiles; g.ipt = h.iters_per_tile; g.tile_order = h.tile_order;
+    g.sk_tiles = h.sk_tiles; g.ipw = h.iters_per_wg; g.grid = h.grid; g.sk_iters = (int)h.sk_iters;
     uint32_t ep = ++g_epoch;
     if (ep == 0) ep = ++g_epoch;                 // 0 is the cleared state of a flag
     g.epoch = ep;

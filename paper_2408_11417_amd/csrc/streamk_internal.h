@@ -14,8 +14,9 @@ struct sk_plan_t {
 
 // Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]
 constexpr size_t SK_FLAG_STRIDE = 128;
+constexpr int SK_GROUP_ROWS = 8;   // tile rows per band of the grouped tile order
 inline size_t sk_ws_status_offset(int grid) { return (size_t)grid * SK_FLAG_STRIDE; }
-inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_FLAG_STRIDE + 128; }
+inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_FLAG_STRIDE + 384; }
 
 // Does the GEMM launcher hold a kernel for this configuration?
 bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k);

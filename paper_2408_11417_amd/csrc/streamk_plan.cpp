@@ -85,11 +85,13 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
     if (policy < 0 || policy > SK_POLICY_SK6_DP_EXT) return SK_ERR_INVALID_ARG;
     sk_config c{};
     if (cfg) c = *cfg;
-    if (c.blk_m < 0 || c.blk_n < 0 || c.blk_k < 0 || c.grid < 0) return SK_ERR_INVALID_ARG;
+    if (c.blk_m < 0 || c.blk_n < 0 || c.blk_k < 0 || c.grid < 0 || c.tile_order < 0) return SK_ERR_INVALID_ARG;
     const int in_dtype = c.in_dtype ? c.in_dtype - 1 : SK_BF16;
     if (!dtype_in_ok(in_dtype)) return SK_ERR_INVALID_ARG;
     const int out_dtype = c.out_dtype ? c.out_dtype - 1 : (in_dtype == SK_FP8_E4M3 ? SK_BF16 : in_dtype);
     if (!dtype_out_ok(out_dtype)) return SK_ERR_INVALID_ARG;
+    const int order = c.tile_order ? c.tile_order - 1 : SK_ORDER_GROUPED;
+    if (order != SK_ORDER_ROW_MAJOR && order != SK_ORDER_GROUPED) return SK_ERR_INVALID_ARG;
     int32_t blk[3] = {c.blk_m, c.blk_n, c.blk_k};
     if (!blk[0] || !blk[1] || !blk[2]) {
         int32_t def[3];
@@ -101,7 +103,7 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
     sk_plan_header h{};
     h.M = M; h.N = N; h.K = K; h.policy = policy;
     h.blk_m = blk[0]; h.blk_n = blk[1]; h.blk_k = blk[2]; h.grid = grid;
-    h.in_dtype = in_dtype; h.out_dtype = out_dtype;
+    h.in_dtype = in_dtype; h.out_dtype = out_dtype; h.tile_order = order;
     // Algorithm 1, lines 2-3
     const int64_t tiles_m = ceil_div(M, blk[0]), tiles_n = ceil_div(N, blk[1]);
     const int64_t ipt = ceil_div(K, blk[2]);
@@ -162,6 +164,24 @@ extern "C" int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t c
     *n = segs.size();
     if (segs.size() > cap) return SK_ERR_INVALID_ARG;
     if (!segs.empty()) std::memcpy(out, segs.data(), segs.size() * sizeof(sk_segment));
+    return SK_OK;
+}
+
+extern "C" int sk_plan_tile_coords(const sk_plan_t* plan, int32_t tile, int32_t* tile_m, int32_t* tile_n) {
+    if (!plan || !tile_m || !tile_n || tile < 0 || tile >= plan->h.tiles) return SK_ERR_INVALID_ARG;
+    const sk_plan_header& h = plan->h;
+    if (h.tile_order == SK_ORDER_ROW_MAJOR) {
+        *tile_m = tile / h.tiles_n;
+        *tile_n = tile % h.tiles_n;
+    } else {
+        // bands of SK_GROUP_ROWS tile rows, walked column by column
+        const int per_band = SK_GROUP_ROWS * h.tiles_n;
+        const int band_row = (tile / per_band) * SK_GROUP_ROWS;
+        const int rows = h.tiles_m - band_row < SK_GROUP_ROWS ? h.tiles_m - band_row : SK_GROUP_ROWS;
+        const int within = tile % per_band;
+        *tile_m = band_row + within % rows;
+        *tile_n = within / rows;
+    }
     return SK_OK;
 }
 

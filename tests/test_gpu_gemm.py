@@ -27,7 +27,7 @@ def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=No
     r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype)
     try:
         # the library's schedule for this very launch equals the oracle's
-        o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"])
+        o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"], r.info["tile_order"])
         assert sk.sk_plan_segments(r.plan) == [tuple(s) for s in o.segments]
         r.run(to_device(A), to_device(B))
         assert r.check() == sk.SK_OK

@@ -25,17 +25,22 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
-def _plan_pair(M, N, K, policy, blk, g):
-    p = sk.sk_plan(M, N, K, policy, blk, g)
+def _plan_pair(M, N, K, policy, blk, g, order=None):
+    p = sk.sk_plan(M, N, K, policy, blk, g, tile_order=order)
     try:
-        return sk.sk_plan_info(p), sk.sk_plan_ranges(p), sk.sk_plan_segments(p), S.plan(M, N, K, policy, *blk, g)
+        info = sk.sk_plan_info(p)
+        o = S.plan(M, N, K, policy, *blk, g, order=info["tile_order"])
+        step = max(1, info["tiles"] // 500)
+        for t in list(range(0, info["tiles"], step)) + [info["tiles"] - 1]:
+            assert sk.sk_plan_tile_coords(p, t) == S.tile_coords(t, info["tiles_m"], info["tiles_n"], info["tile_order"])
+        return info, sk.sk_plan_ranges(p), sk.sk_plan_segments(p), o
     finally:
         sk.sk_plan_destroy(p)
 
 
 def _assert_same(info, ranges, segs, o):
     for key in ("tiles_m", "tiles_n", "tiles", "iters_per_tile", "total_iters", "sk_tiles", "dp_tiles",
-                "sk_iters", "iters_per_wg", "dp_waves", "grid", "blk_m", "blk_n", "blk_k", "policy"):
+                "sk_iters", "iters_per_wg", "dp_waves", "grid", "blk_m", "blk_n", "blk_k", "policy", "tile_order"):
         assert info[key] == o.header[key], key
     assert ranges == [tuple(r) for r in o.ranges]
     assert segs == [tuple(s) for s in o.segments]
@@ -47,7 +52,7 @@ def _assert_same(info, ranges, segs, o):
                  st.sampled_from([8, 32, 64, 128])),
        st.sampled_from([1, 2, 3, 7, 8, 64, 104, 256, 304]), st.integers(0, 7))
 def test_schedule_bit_exact_random(shape, blk, g, policy):
-    _assert_same(*_plan_pair(*shape, policy, blk, g))
+    _assert_same(*_plan_pair(*shape, policy, blk, g, order=(shape[0] + policy) % 2))
 
 
 @pytest.mark.parametrize("policy", range(8))
@@ -67,6 +72,9 @@ def test_plan_defaults_and_errors():
     p = sk.sk_plan(8192, 8192, 8192, sk.SK_POLICY_DP)
     info = sk.sk_plan_info(p)
     assert (info["grid"], info["in_dtype"], info["out_dtype"]) == (256, sk.SK_BF16, sk.SK_BF16)
+    assert info["tile_order"] == sk.SK_ORDER_GROUPED
+    with pytest.raises(sk.StreamKError):
+        sk.sk_plan_tile_coords(p, info["tiles"])
     assert (info["blk_m"], info["blk_n"], info["blk_k"]) == sk.sk_default_tile(8192, 8192, 8192)
     assert info["has_kernel"] == 1
     assert sk.sk_workspace_bytes(p) >= 256 * info["blk_m"] * info["blk_n"] * 4
@@ -75,7 +83,7 @@ def test_plan_defaults_and_errors():
     assert sk.sk_plan_info(p)["out_dtype"] == sk.SK_BF16
     sk.sk_plan_destroy(p)
     for bad in [dict(M=0), dict(policy=8), dict(policy=-1), dict(in_dtype=sk.SK_F32), dict(out_dtype=sk.SK_FP8_E4M3),
-                dict(blk=(-1, 16, 16)), dict(grid=-2)]:
+                dict(blk=(-1, 16, 16)), dict(grid=-2), dict(tile_order=2)]:
         args = dict(M=64, N=64, K=64, policy=0)
         args.update(bad)
         with pytest.raises(sk.StreamKError) as e:

@@ -175,6 +175,30 @@ def test_policy_family_structure(shape, blk, g):
         assert S.makespan_iters(p) <= S.cdiv(T, g) * ipt
 
 
+@settings(max_examples=200, deadline=None)
+@given(st.integers(1, 70), st.integers(1, 70))
+def test_tile_orders_are_bijections_onto_the_tile_grid(tiles_m, tiles_n):
+    T = tiles_m * tiles_n
+    rm = [S.tile_coords(t, tiles_m, tiles_n, S.ORDER_ROW_MAJOR) for t in range(T)]
+    assert rm == [(m, n) for m in range(tiles_m) for n in range(tiles_n)]
+    gr = [S.tile_coords(t, tiles_m, tiles_n, S.ORDER_GROUPED) for t in range(T)]
+    assert sorted(gr) == rm
+    # bands of 8 tile rows, walked column by column: hand construction
+    want = []
+    for band in range(0, tiles_m, 8):
+        rows = min(8, tiles_m - band)
+        want += [(band + r, n) for n in range(tiles_n) for r in range(rows)]
+    assert gr == want
+
+
+def test_grouped_order_makes_compact_blocks():
+    # 32 x 32 tiles (8192^2 at 256 x 256): 32 consecutive indices = 8 rows x 4 columns
+    blk = [S.tile_coords(t, 32, 32, S.ORDER_GROUPED) for t in range(64, 96)]
+    assert {m for m, _ in blk} == set(range(8)) and {n for _, n in blk} == {8, 9, 10, 11}
+    with pytest.raises(ValueError):
+        S.tile_coords(0, 4, 4, 2)
+
+
 def test_bad_arguments_raise():
     with pytest.raises(ValueError):
         S.plan(0, 16, 16, 0, 16, 16, 16, 4)
@@ -201,7 +225,7 @@ def test_executed_schedule_is_exact_on_integer_inputs(shape, blk, g, policy, see
     M, N, K = shape
     A, B = inputs.small_int_pair(M, N, K, inputs.BF16, seed)
     a, b = G.decode_numpy(A, G.BF16), G.decode_numpy(B, G.BF16)
-    p = S.plan(M, N, K, policy, *blk, g)
+    p = S.plan(M, N, K, policy, *blk, g, order=seed % 2)
     assert np.array_equal(simulate.run_plan(p, a, b).astype(np.float64), a @ b)
 
 
