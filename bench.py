@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--policy", type=int, default=-1, help="skip tuning and run this policy only")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 1 GiB device copy a few times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures the single-GPU Stream-K GEMM; --gpus must be 1 (got %d)" % args.gpus)
@@ -54,6 +56,14 @@ def main():
     import paper_2408_11417_amd as sk
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
+        return 0
     stream = torch.cuda.current_stream().cuda_stream
     c = workload(args.workload)
     M, N, K, dt = c["M"], c["N"], c["K"], c["dtype"]
@@ -140,11 +150,12 @@ def main():
         from oracle import gemm as G
         from paper_2408_11417_amd import inputs
         odt = G.F16 if dt == 0 else G.BF16
-        probe_rows = inputs.sample_rows(M, min(M, 8), 0)
+        probe_rows = inputs.sample_rows(M, min(M, 4 * G.threads()), 0)     # short probe to size the sample
+        G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows[:G.threads()])     # (first call also starts the thread pool)
         t0 = time.perf_counter()
         G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows)
         per_row = (time.perf_counter() - t0) / len(probe_rows)
-        n_rows = int(max(8, min(M, 12.0 / max(per_row, 1e-9))))
+        n_rows = int(max(8, min(M, 15.0 / max(per_row, 1e-9))))             # aim at ~15 s, never more than the whole matrix
         rows = inputs.sample_rows(M, n_rows, 1)
         t0 = time.perf_counter()
         G.gemm_fp64(c["A"], c["B"], odt, rows=rows)
