@@ -216,9 +216,21 @@ int bloom_insert(sk_bloom_t* bloom, const sk_bloom_record* rec);
  * Sizes must fit uint32 (INVALID_ARG otherwise). */
 int bloom_query(const sk_bloom_t* bloom, int64_t M, int64_t N, int64_t K, uint32_t* mask_out);
 
+/* n queries at once: sizes is host uint32[3 * n] (M, N, K per query), masks_out host uint32[n]. */
+int bloom_query_many(const sk_bloom_t* bloom, const uint32_t* sizes, size_t n, uint32_t* masks_out);
+
 /* Read access to filter `filter`: *words points at library-owned 64-bit words, valid until
  * bloom_destroy; *n_words = m_bits / 64. */
 int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** words, size_t* n_words);
+
+/* Key for problem sizes that were never profiled.  The filters of Sec. 4.2 are keyed by the exact
+ * (M, N, K), so a size outside the profiled set matches nothing.  This key replaces the size by
+ * what decides which schedule wins under the plan's tile shape and grid: the tile shape, the
+ * number of full waves of tiles (capped at 3), how full the remainder wave is (in quarters of the
+ * grid, rounded up), and floor(log2(iterations per tile)) (capped at 12).  Sizes that share a key
+ * share their winners; records and queries are then made with key[0..2] in place of M, N, K.
+ * key: host uint32[3]. */
+int bloom_shape_key(const sk_plan_t* plan, uint32_t* key);
 
 /* The hash itself (exported for known-answer tests). */
 uint32_t bloom_murmur3_32(const void* key, size_t len, uint32_t seed);
@@ -226,6 +238,9 @@ uint32_t bloom_murmur3_32(const void* key, size_t len, uint32_t seed);
 void bloom_destroy(sk_bloom_t* bloom);
 
 const char* sk_status_str(int status);
+
+/* Text of the last HIP runtime error that made a call of this thread return SK_ERR_HIP. */
+const char* sk_last_hip_error(void);
 
 #ifdef __cplusplus
 }

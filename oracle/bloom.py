@@ -116,6 +116,18 @@ def build(records, m_bits=M_BITS, k_probes=K_PROBES, n_filters=N_FILTERS):
     return bs
 
 
+def shape_key(header):
+    """Key for sizes outside the profiled set (extension; Sec. 4.2 keys by the exact size, which
+    never matches an unseen size): tile shape, full waves of tiles capped at 3, fill of the
+    remainder wave in quarters of the grid rounded up, floor(log2(iterations per tile)) capped at
+    12.  `header` is the plan header of the scheduler oracle."""
+    g = header["grid"]
+    waves = min(header["tiles"] // g, 3)
+    fill = -(-4 * (header["tiles"] % g) // g)
+    lg = min(header["iters_per_tile"].bit_length() - 1, 12)
+    return (header["blk_m"] << 16 | header["blk_n"], waves << 8 | fill, lg << 16 | header["blk_k"])
+
+
 def winner_mask(times, tol):
     """Mask of the policies whose time is within (1 + tol) of the best one (Sec. 4.2 inserts
     the winning configurations; Sec. 5.2's tolerance thresholds widen "winning").

@@ -7,6 +7,13 @@ import fails: there is no fallback path.
 import ctypes
 import os
 
+try:
+    # Device buffers and streams come from PyTorch, which ships its own HIP runtime.  Load it
+    # first so that libstreamk.so binds to the same runtime instance instead of a second one.
+    import torch  # noqa: F401
+except ImportError:
+    pass
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("STREAMK_LIB") or os.path.join(_HERE, "libstreamk.so")   # override: tuning builds
 if not os.path.exists(LIB_PATH):
@@ -26,7 +33,7 @@ SK_ORDER_ROW_MAJOR, SK_ORDER_GROUPED = 0, 1
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
            "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
            "sk_plan_destroy", "sk_default_tile", "bloom_build", "bloom_insert", "bloom_query",
-           "bloom_bits", "bloom_murmur3_32", "bloom_destroy", "sk_status_str")
+           "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
 
 class sk_config(ctypes.Structure):
@@ -79,11 +86,14 @@ _lib.sk_default_tile.argtypes = [_i64, _i64, _i64, _int, ctypes.POINTER(ctypes.c
 _lib.bloom_build.argtypes = [ctypes.POINTER(sk_bloom_record), ctypes.c_size_t, ctypes.POINTER(sk_bloom_params), ctypes.POINTER(_vp)]
 _lib.bloom_insert.argtypes = [_vp, ctypes.POINTER(sk_bloom_record)]
 _lib.bloom_query.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(ctypes.c_uint32)]
+_lib.bloom_query_many.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_bits.argtypes = [_vp, _int, ctypes.POINTER(ctypes.POINTER(ctypes.c_uint64)), ctypes.POINTER(ctypes.c_size_t)]
+_lib.bloom_shape_key.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_murmur3_32.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.c_uint32]
 _lib.bloom_murmur3_32.restype = ctypes.c_uint32
 _lib.bloom_destroy.argtypes = [_vp]
 _lib.bloom_destroy.restype = None
+_lib.sk_last_hip_error.restype = ctypes.c_char_p
 _lib.sk_status_str.argtypes = [_int]
 _lib.sk_status_str.restype = ctypes.c_char_p
 
@@ -91,7 +101,8 @@ _lib.sk_status_str.restype = ctypes.c_char_p
 class StreamKError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__("%s: %s (%d)" % (where, sk_status_str(status), status))
+        detail = " [%s]" % _lib.sk_last_hip_error().decode() if status == SK_ERR_HIP else ""
+        super().__init__("%s: %s (%d)%s" % (where, sk_status_str(status), status, detail))
 
 
 def _check(status, where):
@@ -101,6 +112,10 @@ def _check(status, where):
 
 def sk_status_str(status):
     return _lib.sk_status_str(status).decode()
+
+
+def sk_last_hip_error():
+    return _lib.sk_last_hip_error().decode()
 
 
 def sk_default_tile(M, N, K, in_dtype=SK_BF16):
@@ -196,11 +211,26 @@ def bloom_query(bloom, M, N, K):
     return mask.value
 
 
+def bloom_query_many(bloom, sizes):
+    """sizes: sequence of (M, N, K).  Returns the list of candidate masks."""
+    flat = [int(v) for s in sizes for v in s]
+    arr = (ctypes.c_uint32 * max(len(flat), 1))(*flat)
+    out = (ctypes.c_uint32 * max(len(sizes), 1))()
+    _check(_lib.bloom_query_many(bloom, arr, len(sizes), out), "bloom_query_many")
+    return list(out[:len(sizes)])
+
+
 def bloom_bits(bloom, filt):
     words = ctypes.POINTER(ctypes.c_uint64)()
     n = ctypes.c_size_t()
     _check(_lib.bloom_bits(bloom, filt, ctypes.byref(words), ctypes.byref(n)), "bloom_bits")
     return [words[i] for i in range(n.value)]
+
+
+def bloom_shape_key(plan):
+    key = (ctypes.c_uint32 * 3)()
+    _check(_lib.bloom_shape_key(plan, key), "bloom_shape_key")
+    return tuple(key)
 
 
 def bloom_murmur3_32(key, seed):

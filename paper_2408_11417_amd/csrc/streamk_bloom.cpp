@@ -112,6 +112,24 @@ extern "C" int bloom_query(const sk_bloom_t* bloom, int64_t M, int64_t N, int64_
     return SK_OK;
 }
 
+extern "C" int bloom_query_many(const sk_bloom_t* bloom, const uint32_t* sizes, size_t n, uint32_t* masks_out) {
+    if (!bloom || (!sizes && n) || (!masks_out && n)) return SK_ERR_INVALID_ARG;
+    for (size_t q = 0; q < n; q++) {
+        uint32_t mask = 0;
+        for (uint32_t p = 0; p < bloom->n_filters; p++) {
+            const uint64_t* w = bloom->filters[p].data();
+            bool hit = true;
+            for (uint32_t i = 0; i < bloom->k_probes && hit; i++) {
+                const uint32_t bit = hash_key(sizes[3 * q], sizes[3 * q + 1], sizes[3 * q + 2], p * bloom->k_probes + i) % bloom->m_bits;
+                hit = (w[bit >> 6] >> (bit & 63)) & 1u;
+            }
+            if (hit) mask |= 1u << p;
+        }
+        masks_out[q] = mask;
+    }
+    return SK_OK;
+}
+
 extern "C" int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** words, size_t* n_words) {
     if (!bloom || !words || !n_words || filter < 0 || (uint32_t)filter >= bloom->n_filters) return SK_ERR_INVALID_ARG;
     *words = bloom->filters[filter].data();

@@ -689,7 +689,15 @@ KernelEntry* find_kernel(int dtype, int bm, int bn, int bk) {
 
 std::atomic<uint32_t> g_epoch{0};
 
+thread_local hipError_t g_last_hip = hipSuccess;   // last failing HIP call of this thread
+inline bool hip_ok(hipError_t e) {
+    if (e != hipSuccess) g_last_hip = e;
+    return e == hipSuccess;
+}
+
 }  // namespace
+
+extern "C" const char* sk_last_hip_error(void) { return hipGetErrorString(g_last_hip); }
 
 bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k) {
     return find_kernel(in_dtype, blk_m, blk_n, blk_k) != nullptr;
@@ -698,8 +706,8 @@ bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k) {
 extern "C" int sk_plan_set_workspace(sk_plan_t* plan, void* dev_ptr, size_t bytes) {
     if (!plan || !dev_ptr) return SK_ERR_INVALID_ARG;
     if (bytes < sk_workspace_bytes(plan) || (reinterpret_cast<uintptr_t>(dev_ptr) & 255)) return SK_ERR_WORKSPACE;
-    if (hipMemset(dev_ptr, 0, sk_ws_partials_offset(plan->h.grid)) != hipSuccess) return SK_ERR_HIP;
-    if (hipDeviceSynchronize() != hipSuccess) return SK_ERR_HIP;
+    if (!hip_ok(hipMemset(dev_ptr, 0, sk_ws_partials_offset(plan->h.grid)))) return SK_ERR_HIP;
+    if (!hip_ok(hipDeviceSynchronize())) return SK_ERR_HIP;
     plan->workspace = dev_ptr;
     plan->workspace_bytes = bytes;
     return SK_OK;
@@ -707,13 +715,13 @@ extern "C" int sk_plan_set_workspace(sk_plan_t* plan, void* dev_ptr, size_t byte
 
 extern "C" int sk_plan_check(const sk_plan_t* plan, void* stream) {
     if (!plan) return SK_ERR_INVALID_ARG;
-    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SK_ERR_HIP;
+    if (!hip_ok(hipStreamSynchronize(static_cast<hipStream_t>(stream)))) return SK_ERR_HIP;
     if (!plan->workspace) return SK_OK;
     uint32_t* st = reinterpret_cast<uint32_t*>(static_cast<char*>(plan->workspace) + sk_ws_status_offset(plan->h.grid));
     uint32_t v = 0;
-    if (hipMemcpy(&v, st, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) return SK_ERR_HIP;
+    if (!hip_ok(hipMemcpy(&v, st, sizeof v, hipMemcpyDeviceToHost))) return SK_ERR_HIP;
     if (v) {
-        if (hipMemset(st, 0, sizeof v) != hipSuccess) return SK_ERR_HIP;
+        if (!hip_ok(hipMemset(st, 0, sizeof v))) return SK_ERR_HIP;
         return SK_ERR_TIMEOUT;
     }
     return SK_OK;
@@ -736,12 +744,12 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     if (e->max_resident.load() < 0) {
         // first use on this process: allow the large LDS footprint and ask how many workgroups fit at once
         for (kernel_fn f : {e->aligned, e->generic})
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(f), hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes) != hipSuccess)
+            if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(f), hipFuncAttributeMaxDynamicSharedMemorySize, e->lds_bytes)))
                 return SK_ERR_HIP;
         int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        if (!hip_ok(hipGetDevice(&dev)) || !hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)))
             return SK_ERR_HIP;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(e->generic), e->threads, e->lds_bytes) != hipSuccess)
+        if (!hip_ok(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(e->generic), e->threads, e->lds_bytes)))
             return SK_ERR_HIP;
         e->max_resident.store(per_cu * cus);
     }
@@ -763,5 +771,5 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.spin_limit = plan->spin_limit;
     g.out_dtype = h.out_dtype;
     hipLaunchKernelGGL(fn, dim3(h.grid), dim3(e->threads), e->lds_bytes, static_cast<hipStream_t>(stream), g);
-    return hipGetLastError() == hipSuccess ? SK_OK : SK_ERR_HIP;
+    return hip_ok(hipGetLastError()) ? SK_OK : SK_ERR_HIP;
 }

@@ -62,21 +62,35 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
 
 extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_blk) {
     if (!out_blk || M < 1 || N < 1 || K < 1 || !dtype_in_ok(in_dtype)) return SK_ERR_INVALID_ARG;
-    // Dispatcher heuristic: big tiles when there are enough of them to fill 256 compute
-    // units, smaller ones otherwise; skinny M gets a tile as tall as M.
-    int bm, bn, bk = 64;
-    if (M <= 16) { bm = 16; bn = 128; }
-    else if (M <= 32) { bm = 32; bn = 128; }
-    else if (M <= 64) { bm = 64; bn = 128; }
-    else {
-        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
-        const int64_t t256x128 = ceil_div(M, 256) * ceil_div(N, 128);
-        if (t256 >= 512 && N > 128) { bm = 256; bn = 256; }
-        else if (t256x128 >= 256 && M > 128) { bm = 256; bn = 128; }
-        else { bm = 128; bn = 128; }
+    // Dispatcher: a small cost model over the tile shapes that have a kernel.  For each shape it
+    // estimates the time of the better of (a) whole tiles in waves over the grid and (b) the
+    // iterations split evenly over the grid plus the cost of exchanging partial tiles, and keeps
+    // the cheapest.  Constants (sustained TFLOP/s of each kernel with the grid full, microseconds
+    // to drain / store a tile and to park or fetch a partial) were read off timing runs on MI355X.
+    struct Cand { int bm, bn; double tflops; };
+    static const Cand cands[] = {{256, 256, 1150.}, {256, 128, 890.}, {128, 128, 790.}, {64, 128, 570.}, {32, 128, 300.}};
+    const int bk = 64, grid = 256;
+    const double ipt = (double)ceil_div(K, bk);
+    double best_t = 0;
+    int best = -1;
+    for (int i = 0; i < (int)(sizeof cands / sizeof cands[0]); i++) {
+        const Cand& c = cands[i];
+        const double tiles = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
+        const double t_iter = 2.0 * c.bm * c.bn * bk * grid / (c.tflops * 1e12) * 1e6;   // us per k-iteration
+        const double c_tile = 1.5 + c.bm * c.bn * 2 / 60e3;
+        const double c_part = 2.0 + c.bm * c.bn * 4 / 40e3;
+        const double waves = (double)((int64_t)((tiles + grid - 1) / grid));
+        const double t_dp = waves * (ipt * t_iter + c_tile);
+        const double ipw = (double)((int64_t)((tiles * ipt + grid - 1) / grid));
+        double split = grid / tiles;
+        if (split > ipt) split = ipt;
+        if (split < 1) split = 1;
+        const bool ragged = ((int64_t)tiles % grid) != 0;
+        const double t_sk = ipw * t_iter + c_tile * (tiles > grid ? tiles / grid : 1.0) + (ragged ? c_part * (1 + split) : 0.0);
+        const double t = t_dp < t_sk ? t_dp : t_sk;
+        if (best < 0 || t < best_t) { best = i; best_t = t; }
     }
-    (void)K;
-    out_blk[0] = bm; out_blk[1] = bn; out_blk[2] = bk;
+    out_blk[0] = cands[best].bm; out_blk[1] = cands[best].bn; out_blk[2] = bk;
     return SK_OK;
 }
 
@@ -182,6 +196,22 @@ extern "C" int sk_plan_tile_coords(const sk_plan_t* plan, int32_t tile, int32_t*
         *tile_m = band_row + within % rows;
         *tile_n = within / rows;
     }
+    return SK_OK;
+}
+
+extern "C" int bloom_shape_key(const sk_plan_t* plan, uint32_t* key) {
+    if (!plan || !key) return SK_ERR_INVALID_ARG;
+    const sk_plan_header& h = plan->h;
+    uint32_t waves = (uint32_t)(h.tiles / h.grid);
+    if (waves > 3) waves = 3;
+    const uint32_t rem = (uint32_t)(h.tiles % h.grid);
+    const uint32_t fill = (4 * rem + (uint32_t)h.grid - 1) / (uint32_t)h.grid;   // 0 = no remainder wave, 1..4 quarters
+    uint32_t lg = 0;
+    for (uint32_t v = (uint32_t)h.iters_per_tile; v > 1; v >>= 1) lg++;
+    if (lg > 12) lg = 12;
+    key[0] = (uint32_t)h.blk_m << 16 | ((uint32_t)h.blk_n & 0xFFFFu);
+    key[1] = waves << 8 | fill;
+    key[2] = lg << 16 | ((uint32_t)h.blk_k & 0xFFFFu);
     return SK_OK;
 }
 

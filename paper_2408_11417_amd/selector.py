@@ -1,0 +1,172 @@
+"""Bloom-filter policy selection on top of a tuning sweep (Sec. 4.2 of the paper).
+
+Records from `sweep.py` say how long each of the seven policies took for a problem size.  The
+policies within a tolerance of the best are that size's winners; the size (or, for sizes that
+were never profiled, its shape key, see bloom_shape_key) is inserted into the filter of each
+winner.  A query returns the candidate policies; the profiler then times only those, or - when no
+timing is wanted - the candidate that won most often in the build set is taken.
+
+    python -m paper_2408_11417_amd.selector --sweep gpurun_out/sweep_bf16.json --split 400
+
+prints, for tolerances 0 / 5 % / 20 %: false negatives on the build split, pruning rate, and on
+the held-out split the ratio selected / best and the share of shapes at >= 90 % of the best.
+All filter work goes through the C library; nothing here needs a GPU.
+"""
+import argparse
+import json
+import sys
+import time
+
+from . import binding as sk
+
+N_POL = sk.SK_NUM_POLICIES
+
+
+def winner_mask(times_ns, tol):
+    """Bit p set iff policy p is within (1 + tol) of the fastest (integer arithmetic in permille)."""
+    best = min(times_ns)
+    permille = int(round(tol * 1000))
+    return sum(1 << p for p, t in enumerate(times_ns) if t * 1000 <= best * (1000 + permille))
+
+
+def shape_key(M, N, K, tile=None, grid=256, in_dtype=sk.SK_BF16):
+    plan = sk.sk_plan(M, N, K, sk.SK_POLICY_DP, tuple(tile) if tile else None, grid, in_dtype)
+    try:
+        return sk.bloom_shape_key(plan)
+    finally:
+        sk.sk_plan_destroy(plan)
+
+
+def fallback_policy(tiles, grid=256):
+    """Used when no filter knows the key: nothing to balance if the tiles fill whole waves,
+    otherwise one Stream-K batch over the remainder wave."""
+    return sk.SK_POLICY_DP if tiles % grid == 0 else sk.SK_POLICY_SK1_DP
+
+
+class PolicySelector:
+    """Filters built from sweep records.  mode 'exact' keys by (M, N, K) as the paper does;
+    mode 'shape' keys by bloom_shape_key so that unseen sizes can be answered."""
+
+    def __init__(self, records, tol=0.2, mode="shape", grid=256):
+        self.tol, self.mode, self.grid = tol, mode, grid
+        self.wins = [0] * N_POL
+        merged = {}
+        for r in records:
+            t = r["time_ns"]
+            self.wins[t.index(min(t))] += 1
+            key = self.key_of(r)
+            merged[key] = merged.get(key, 0) | winner_mask(t, tol)
+        self.inserted = merged
+        self.bloom = sk.bloom_build([(k[0], k[1], k[2], m) for k, m in merged.items()])
+
+    def key_of(self, r):
+        if self.mode == "exact":
+            return (r["M"], r["N"], r["K"])
+        return shape_key(r["M"], r["N"], r["K"], r.get("tile"), self.grid)
+
+    def candidates(self, r):
+        return sk.bloom_query(self.bloom, *self.key_of(r))
+
+    def select(self, r, times_ns=None):
+        """(policy, candidate mask, used_fallback).  With times: the fastest candidate (the profiler
+        ran only the candidates); without: the candidate with most wins in the build set."""
+        mask = self.candidates(r)
+        cands = [p for p in range(N_POL) if (mask >> p) & 1]
+        fell_back = not cands
+        if fell_back:
+            cands = [fallback_policy(r["tiles"], self.grid)]
+        if times_ns is not None:
+            return min(cands, key=lambda p: times_ns[p]), mask, fell_back
+        return max(cands, key=lambda p: (self.wins[p], -p)), mask, fell_back
+
+    def close(self):
+        sk.bloom_destroy(self.bloom)
+
+
+def evaluate(records, split, tol, mode):
+    build, held = records[:split], records[split:]
+    sel = PolicySelector(build, tol, mode)
+    out = {"tol": tol, "mode": mode, "build_sizes": len(build), "held_out_sizes": len(held),
+           "distinct_keys": len(sel.inserted)}
+    # build split: every inserted (key, policy) must come back; count what the filters prune
+    fn = kept = kept_non_dp = 0
+    for r in build:
+        want = winner_mask(r["time_ns"], tol)
+        got = sel.candidates(r)
+        fn += bin(want & ~got).count("1")
+        kept += bin(got).count("1")
+        kept_non_dp += bin(got >> 1).count("1")
+    out["false_negatives"] = fn
+    out["pruning_rate_build"] = 1 - kept / (N_POL * len(build))
+    out["pruning_rate_build_non_dp"] = 1 - kept_non_dp / ((N_POL - 1) * len(build))
+    # held-out split
+    ratios, ratios_static, kept, miss, fallbacks, dist_kept, dist_all = [], [], 0, 0, 0, 0, 0
+    t0 = time.perf_counter()
+    for r in held:
+        sel.candidates(r)
+    out["query_us_incl_key"] = (time.perf_counter() - t0) / max(len(held), 1) * 1e6
+    for r in held:
+        t = r["time_ns"]
+        p, mask, fb = sel.select(r, t)
+        ps, _, _ = sel.select(r)
+        cands = [q for q in range(N_POL) if (mask >> q) & 1] or [p]
+        kept += len(cands)
+        fallbacks += fb
+        miss += t.index(min(t)) not in cands and min(t) < min(t[q] for q in cands)
+        ratios.append(min(t) / t[p])
+        ratios_static.append(min(t) / t[ps])
+        dist_kept += len({r["sk_tiles"][q] for q in cands})
+        dist_all += len(set(r["sk_tiles"]))
+    n = max(len(held), 1)
+    out.update({
+        "held_pruning_rate": 1 - kept / (N_POL * n),
+        "held_pruning_rate_distinct_schedules": 1 - dist_kept / max(dist_all, 1),
+        "held_fallbacks": fallbacks, "held_best_not_among_candidates": miss,
+        "held_share_ge_0.9_of_best": sum(x >= 0.9 for x in ratios) / n,
+        "held_mean_ratio": sum(ratios) / n, "held_min_ratio": min(ratios) if ratios else None,
+        "held_share_ge_0.9_no_timing": sum(x >= 0.9 for x in ratios_static) / n,
+    })
+    sel.close()
+    return out
+
+
+def sweep_statistics(records):
+    """Winner shares and tolerance curve in the style of Sec. 5.2."""
+    n = len(records)
+    wins = [0] * N_POL
+    gains = []
+    for r in records:
+        t = r["time_ns"]
+        w = t.index(min(t))
+        wins[w] += 1
+        if w != 0:
+            gains.append(t[0] / min(t) - 1)
+    out = {"sizes": n, "winner_share": {sk.POLICY_NAMES[p]: wins[p] / n for p in range(N_POL)},
+           "stream_k_winner_mean_gain_over_dp": sum(gains) / len(gains) if gains else 0.0,
+           "stream_k_winner_max_gain_over_dp": max(gains) if gains else 0.0}
+    for tol in (0.0, 0.05, 0.1, 0.2):
+        out["share_stream_k_within_%g_of_dp" % tol] = sum(
+            min(r["time_ns"][1:]) * 1000 <= r["time_ns"][0] * (1000 + int(tol * 1000)) for r in records) / n
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--sweep", required=True)
+    ap.add_argument("--split", type=int, default=400)
+    ap.add_argument("--out", default="")
+    args = ap.parse_args()
+    records = json.load(open(args.sweep))["records"]
+    report = {"statistics": sweep_statistics(records), "evaluations": []}
+    for mode in ("exact", "shape"):
+        for tol in (0.0, 0.05, 0.2):
+            report["evaluations"].append(evaluate(records, args.split, tol, mode))
+    text = json.dumps(report, indent=1)
+    print(text)
+    if args.out:
+        open(args.out, "w").write(text)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,128 @@
+"""Tuning sweep: time every scheduling policy on a list of GEMM shapes and record the winners.
+
+This is the stand-in for the profiler run of the paper (Sec. 5.1): for each problem size all seven
+Stream-K++ policies are launched with warm-up + timed repetitions (50 + 50 for short kernels, fewer
+for long ones) and the mean kernel time is kept.  The output feeds `selector.py`, which builds the
+Bloom filters (Sec. 4.2) from the winners and evaluates them on held-out shapes.
+
+    python -m paper_2408_11417_amd.sweep --shapes 500 --seed 4 --out gpurun_out/sweep.json
+
+Needs a GPU.  Inputs are seeded synthetic bf16 matrices, uniform in [-1, 1], carved out of two
+device pools that are filled once.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+
+def time_policy(sk, torch, plan, dA, dB, dD, stream, est_ms):
+    """Mean milliseconds per launch; repetitions follow the paper's 50 + 50 protocol for kernels up
+    to 0.2 ms and shrink to >= 5 + 5 (about 20 ms of timed work) for longer ones."""
+    reps = 50 if est_ms <= 0.2 else max(5, int(20.0 / est_ms))
+    for _ in range(reps):
+        sk.sk_gemm(dA, dB, dD, plan, stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        sk.sk_gemm(dA, dB, dD, plan, stream)
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps, reps
+
+
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25):
+    import torch
+    import paper_2408_11417_amd as sk
+
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    tdt = torch.bfloat16 if dtype_code == sk.SK_BF16 else torch.float16
+    max_a = max(M * K for M, N, K in shapes)
+    max_b = max(K * N for M, N, K in shapes)
+    max_d = max(M * N for M, N, K in shapes)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+
+    def pool(n):
+        out = torch.empty(n, dtype=tdt, device="cuda")
+        step = 1 << 26
+        for i in range(0, n, step):
+            m = min(step, n - i)
+            out[i:i + m] = (torch.rand(m, device="cuda", generator=gen) * 2 - 1).to(tdt)
+        return out
+
+    pa, pb = pool(max_a), pool(max_b)
+    pd = torch.empty(max_d, dtype=tdt, device="cuda")
+    pd2 = torch.empty(max_d, dtype=tdt, device="cuda")
+    ws_bytes = 256 * 256 * 256 * 4 + (1 << 16)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+
+    records, t_start = [], time.time()
+    for idx, (M, N, K) in enumerate(shapes):
+        plans, infos = [], []
+        for p in range(sk.SK_NUM_POLICIES):
+            plan = sk.sk_plan(M, N, K, p, None, 256, dtype_code, dtype_code)
+            assert sk.sk_workspace_bytes(plan) <= ws_bytes
+            sk.sk_plan_set_workspace(plan, ws_ptr, ws_bytes)
+            plans.append(plan)
+            infos.append(sk.sk_plan_info(plan))
+        # policies whose Stream-K region covers the same number of tiles are the same schedule
+        by_sched, times, reps_used = {}, [0.0] * 7, [0] * 7
+        dA, dB, dD = pa.data_ptr(), pb.data_ptr(), pd.data_ptr()
+        for p in range(sk.SK_NUM_POLICIES):
+            key = infos[p]["sk_tiles"]
+            if key not in by_sched:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                sk.sk_gemm(dA, dB, dD, plans[p], stream)          # first touch
+                e0.record()
+                sk.sk_gemm(dA, dB, dD, plans[p], stream)
+                e1.record()
+                e1.synchronize()
+                by_sched[key] = time_policy(sk, torch, plans[p], dA, dB, dD, stream, e0.elapsed_time(e1))
+            times[p], reps_used[p] = by_sched[key]
+        rec = {"M": M, "N": N, "K": K, "tile": [infos[0]["blk_m"], infos[0]["blk_n"], infos[0]["blk_k"]],
+               "tiles": infos[0]["tiles"], "iters_per_tile": infos[0]["iters_per_tile"],
+               "sk_tiles": [i["sk_tiles"] for i in infos], "time_ns": [int(round(t * 1e6)) for t in times],
+               "reps": reps_used, "distinct_schedules": len(by_sched)}
+        if check_every and idx % check_every == 0:
+            # consistency of the policies among themselves: all-Stream-K against data-parallel
+            sk.sk_gemm(dA, dB, pd.data_ptr(), plans[0], stream)
+            sk.sk_gemm(dA, dB, pd2.data_ptr(), plans[6], stream)
+            assert sk.sk_plan_check(plans[6], stream) == sk.SK_OK
+            a, b = pd[:M * N].float(), pd2[:M * N].float()
+            rec["dp_vs_allsk_maxdiff_over_rms"] = float((a - b).abs().max() / a.pow(2).mean().sqrt())
+        records.append(rec)
+        for plan in plans:
+            sk.sk_plan_destroy(plan)
+        if verbose and (idx % 10 == 0 or idx == len(shapes) - 1):
+            best = min(times)
+            print("[%4d/%d %6.0fs] %5dx%5dx%5d tile %s T=%d  best %.4f ms (%s) %.0f TFLOP/s  dp %.4f" % (
+                idx + 1, len(shapes), time.time() - t_start, M, N, K, rec["tile"], rec["tiles"], best,
+                sk.POLICY_NAMES[times.index(best)], 2.0 * M * N * K / best / 1e9, times[0]), flush=True)
+        if out_path and (idx % 50 == 49 or idx == len(shapes) - 1):
+            with open(out_path, "w") as f:
+                json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256, "records": records}, f)
+    return records
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--shapes", type=int, default=500)
+    ap.add_argument("--seed", type=int, default=4)
+    ap.add_argument("--out", default="gpurun_out/sweep.json")
+    ap.add_argument("--first", type=int, default=0, help="only the first N shapes (smoke runs)")
+    args = ap.parse_args()
+    from paper_2408_11417_amd import inputs
+    shapes = inputs.sweep_shapes(args.shapes, args.seed)
+    if args.first:
+        shapes = shapes[:args.first]
+    run(shapes, args.out)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -138,6 +138,29 @@ def test_bloom_bits_and_queries_bit_exact_with_oracle(params):
     sk.bloom_destroy(b)
 
 
+@settings(max_examples=200, deadline=None)
+@given(st.tuples(st.integers(1, 20000), st.integers(1, 20000), st.integers(1, 70000)),
+       st.sampled_from([(256, 256, 64), (128, 128, 64), (32, 128, 64), (16, 128, 32)]),
+       st.sampled_from([7, 104, 256]))
+def test_shape_key_bit_exact_with_oracle(shape, blk, g):
+    p = sk.sk_plan(*shape, 0, blk, g)
+    o = S.plan(*shape, 0, *blk, g)
+    assert sk.bloom_shape_key(p) == Bm.shape_key(o.header)
+    sk.sk_plan_destroy(p)
+
+
+def test_shape_key_values_by_hand():
+    # 3840 x 4224 x 4096 at 256 x 128 x 64 on 256 workgroups: 495 tiles = 1 full wave + 239 tiles
+    # (239 / 256 -> 4 quarters), 64 iterations per tile -> log2 = 6
+    p = sk.sk_plan(3840, 4224, 4096, 0, (256, 128, 64), 256)
+    assert sk.bloom_shape_key(p) == (256 << 16 | 128, 1 << 8 | 4, 6 << 16 | 64)
+    sk.sk_plan_destroy(p)
+    # 8192^3 at 256 x 256 x 64: 1024 tiles = 4 waves (capped at 3), no remainder, 128 iterations -> 7
+    p = sk.sk_plan(8192, 8192, 8192, 0, (256, 256, 64), 256)
+    assert sk.bloom_shape_key(p) == (256 << 16 | 256, 3 << 8 | 0, 7 << 16 | 64)
+    sk.sk_plan_destroy(p)
+
+
 def test_bloom_insert_after_build_and_errors():
     b = sk.bloom_build([])
     assert sk.bloom_query(b, 512, 512, 512) == 0
