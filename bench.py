@@ -16,7 +16,7 @@ import time
 
 import numpy as np
 
-PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6}    # dense MFMA peak of MI355X
+PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "e4m3": 5033.2}    # dense MFMA peak of MI355X
 
 
 def workload(name):
@@ -27,6 +27,9 @@ def workload(name):
     elif name == "cfg5":
         c = inputs.config5(inputs.BF16)
         c["label"] = "cfg5: bf16 GEMM 8192^3, U[-1,1], seed 3"
+    elif name == "cfg5_fp8":
+        c = inputs.config5(inputs.E4M3)
+        c["label"] = "cfg5: fp8 e4m3 GEMM 8192^3, bf16 output, U[-1,1], seed 3"
     elif name == "cfg1":
         c = inputs.config1()
         c["label"] = "cfg1: fp16 GEMM 512^3, 128x128x32 tiles, U[-1,1], seed 0"
@@ -67,10 +70,10 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     c = workload(args.workload)
     M, N, K, dt = c["M"], c["N"], c["K"], c["dtype"]
-    dtype_name = {0: "f16", 1: "bf16"}[dt]
+    dtype_name = {0: "f16", 1: "bf16", 2: "e4m3"}[dt]
     flops = 2.0 * M * N * K
-    dA = torch.from_numpy(c["A"].view(np.int16)).cuda()
-    dB = torch.from_numpy(c["B"].view(np.int16)).cuda()
+    dA = torch.from_numpy(c["A"].view(np.int16 if dt != 2 else np.uint8)).cuda()
+    dB = torch.from_numpy(c["B"].view(np.int16 if dt != 2 else np.uint8)).cuda()
     D = torch.empty((M, N), dtype=torch.int16, device="cuda")
 
     plans, keep = {}, []
@@ -149,7 +152,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import gemm as G
         from paper_2408_11417_amd import inputs
-        odt = G.F16 if dt == 0 else G.BF16
+        odt = {0: G.F16, 1: G.BF16, 2: G.E4M3}[dt]
         probe_rows = inputs.sample_rows(M, min(M, 4 * G.threads()), 0)     # short probe to size the sample
         G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows[:G.threads()])     # (first call also starts the thread pool)
         t0 = time.perf_counter()

@@ -26,6 +26,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16;
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
@@ -72,6 +74,21 @@ template <> struct Mfma<SK_F16, 16> {
     }
 };
 
+// fp8 (e4m3): the scaled 8-bit instruction with both block scales at 2^0 (biased exponent 127);
+// per lane 32 consecutive k (8 registers) of row / column l % MF starting at 32 * (l / MF).
+template <> struct Mfma<SK_FP8_E4M3, 32> {
+    typedef f32x16 Acc;
+    static __device__ __forceinline__ Acc run(i32x8 a, i32x8 b, Acc c) {
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
+    }
+};
+template <> struct Mfma<SK_FP8_E4M3, 16> {
+    typedef f32x4 Acc;
+    static __device__ __forceinline__ Acc run(i32x8 a, i32x8 b, Acc c) {
+        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
+    }
+};
+
 template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MF_, int NSA_, int NSB_ = NSA_>
 struct Cfg {
     static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MF = MF_;
@@ -79,14 +96,19 @@ struct Cfg {
     static constexpr int NW = WM * WN, THREADS = 64 * NW;
     static constexpr int WTM = BM / WM, WTN = BN / WN;   // tile of one wave
     static constexpr int MI = WTM / MF, NI = WTN / MF;   // matrix-core blocks per wave tile
-    static constexpr int KG = 64 / MF;                   // groups of 8 k across the lanes
-    static constexpr int KM = 8 * KG;                    // k per instruction
+    static constexpr bool FP8 = DT == SK_FP8_E4M3;
+    static constexpr int ES = FP8 ? 1 : 2;               // bytes per input element
+    static constexpr int PE = 16 / ES;                   // elements per 16-byte piece
+    static constexpr int KPL = FP8 ? 32 : 8;             // consecutive k per lane per instruction
+    static constexpr int APL = KPL / PE;                 // A pieces per lane per instruction
+    static constexpr int KG = 64 / MF;                   // groups of KPL k across the lanes
+    static constexpr int KM = KPL * KG;                  // k per instruction
     static constexpr int KK = BK / KM;
     static constexpr int ACC = MF * MF / 64;             // accumulator registers per block
     // LDS: a ring of NSA A tiles (BM rows of CPA 16-byte pieces) followed by a ring of NSB B tiles
     // (BK rows of CPB pieces), no padding.  A may be one stage deeper than B: its loads then run
     // two iterations ahead and only the B tile has to arrive within one iteration.
-    static constexpr int CPA = BK / 8, CPB = BN / 8;
+    static constexpr int CPA = BK / PE, CPB = BN / PE;
     static constexpr int A_PIECES = BM * CPA, B_PIECES = BK * CPB;
     static constexpr int A_BYTES = A_PIECES * 16, B_BYTES = B_PIECES * 16;
     static constexpr int B_RING = NSA * A_BYTES;         // byte offset of the B ring
@@ -124,9 +146,11 @@ template <int CPA> __device__ __forceinline__ int swz_a(int r) {
     if (CPA == 4) return (r >> 1) & 3;
     return (r & 7) ^ ((r >> 3) & 1);
 }
-// B: piece c of row k sits at position c ^ swz_b(k): rows k..k+3, read together by one transposing
+// B: piece c of row k sits at position c ^ swz_b<C::FP8>(k): rows k..k+3, read together by one transposing
 // read, land on different 32-byte and different 64-byte bank groups.
-__device__ __forceinline__ int swz_b(int k) {
+// (8-bit elements: one transposing read covers 8 rows; rows k..k+7 go to 8 different 32-byte groups.)
+template <bool FP8> __device__ __forceinline__ int swz_b(int k) {
+    if (FP8) return (k & 7) << 1;
     const int k0 = k & 1, k1 = (k >> 1) & 1;
     return (k0 << 1) | (k1 << 2) | (k0 << 3);
 }
@@ -159,20 +183,22 @@ __device__ __forceinline__ int logical_wg(int hw, int grid) {
     return (grid % 8 == 0) ? (hw % 8) * (grid / 8) + hw / 8 : hw;
 }
 
-template <bool ALIGNED>
-__device__ __forceinline__ uint4 load8(const u16* __restrict__ base, int row, int col, int rows, int cols) {
-    // 8 consecutive 16-bit elements of a row-major matrix with `cols` columns, zero beyond its edges
+template <int ES, bool ALIGNED>
+__device__ __forceinline__ uint4 load_piece(const unsigned char* __restrict__ base, int row, int col, int rows, int cols) {
+    // 16 bytes = 16 / ES consecutive elements of a row-major matrix with `cols` columns, zero beyond its edges
     uint4 v = make_uint4(0, 0, 0, 0);
     if (row < rows) {
-        const u16* p = base + (size_t)((uint32_t)row * (uint32_t)cols + (uint32_t)col);
+        const unsigned char* p = base + (size_t)((uint32_t)row * (uint32_t)cols + (uint32_t)col) * ES;
         if (ALIGNED) {
             if (col < cols) v = *reinterpret_cast<const uint4*>(p);
         } else {
-            u16 e[8];
+            unsigned char e[16];
 #pragma unroll
-            for (int i = 0; i < 8; i++) e[i] = (col + i < cols) ? p[i] : (u16)0;
-            v.x = e[0] | (uint32_t)e[1] << 16; v.y = e[2] | (uint32_t)e[3] << 16;
-            v.z = e[4] | (uint32_t)e[5] << 16; v.w = e[6] | (uint32_t)e[7] << 16;
+            for (int i = 0; i < 16; i++) e[i] = (col + i / ES < cols) ? p[i] : (unsigned char)0;
+            v.x = e[0] | (uint32_t)e[1] << 8 | (uint32_t)e[2] << 16 | (uint32_t)e[3] << 24;
+            v.y = e[4] | (uint32_t)e[5] << 8 | (uint32_t)e[6] << 16 | (uint32_t)e[7] << 24;
+            v.z = e[8] | (uint32_t)e[9] << 8 | (uint32_t)e[10] << 16 | (uint32_t)e[11] << 24;
+            v.w = e[12] | (uint32_t)e[13] << 8 | (uint32_t)e[14] << 16 | (uint32_t)e[15] << 24;
         }
     }
     return v;
@@ -182,21 +208,21 @@ __device__ __forceinline__ uint4 load8(const u16* __restrict__ base, int row, in
 template <class C, bool ALIGNED>
 __device__ __forceinline__ void fill_stage_staged(const GemmArgs& g, int m0, int n0, int kit, unsigned char* a_stage, unsigned char* b_stage) {
     const int tid = threadIdx.x;
-    const u16* A = static_cast<const u16*>(g.A);
-    const u16* B = static_cast<const u16*>(g.B);
+    const unsigned char* A = static_cast<const unsigned char*>(g.A);
+    const unsigned char* B = static_cast<const unsigned char*>(g.B);
     const int k0 = kit * C::BK;
     uint4 ra[C::CA], rb[C::CB];
 #pragma unroll
     for (int i = 0; i < C::CA; i++) {
         const int p = tid + i * C::THREADS;
         if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES)
-            ra[i] = load8<ALIGNED>(A, m0 + p / C::CPA, k0 + (p % C::CPA) * 8, g.M, g.K);
+            ra[i] = load_piece<C::ES, ALIGNED>(A, m0 + p / C::CPA, k0 + (p % C::CPA) * C::PE, g.M, g.K);
     }
 #pragma unroll
     for (int i = 0; i < C::CB; i++) {
         const int p = tid + i * C::THREADS;
         if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES)
-            rb[i] = load8<ALIGNED>(B, k0 + p / C::CPB, n0 + (p % C::CPB) * 8, g.K, g.N);
+            rb[i] = load_piece<C::ES, ALIGNED>(B, k0 + p / C::CPB, n0 + (p % C::CPB) * C::PE, g.K, g.N);
     }
     uint4* sA = reinterpret_cast<uint4*>(a_stage);
     uint4* sB = reinterpret_cast<uint4*>(b_stage);
@@ -208,7 +234,7 @@ __device__ __forceinline__ void fill_stage_staged(const GemmArgs& g, int m0, int
 #pragma unroll
     for (int i = 0; i < C::CB; i++) {
         const int p = tid + i * C::THREADS, k = p / C::CPB;
-        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES) sB[k * C::CPB + ((p % C::CPB) ^ swz_b(k))] = rb[i];
+        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES) sB[k * C::CPB + ((p % C::CPB) ^ swz_b<C::FP8>(k))] = rb[i];
     }
 }
 
@@ -226,23 +252,23 @@ template <class C> struct DmaMap {
             const int r = p / C::CPA, c = (p % C::CPA) ^ swz_a<C::CPA>(r);
             int row = m0 + r;
             row = row < g.M ? row : g.M - 1;
-            a_off[j] = ((uint32_t)row * (uint32_t)g.K + 8u * c) * 2u;
+            a_off[j] = ((uint32_t)row * (uint32_t)g.K + (uint32_t)(C::PE * c)) * C::ES;
         }
 #pragma unroll
         for (int j = 0; j < C::B_LD; j++) {
             const int p = (j * C::NW + wave) * 64 + lane;
-            const int k = p / C::CPB, c = (p % C::CPB) ^ swz_b(k);
-            int col = n0 + 8 * c;
-            col = col < g.N ? col : g.N - 8;
-            b_off[j] = ((uint32_t)k * (uint32_t)g.N + (uint32_t)col) * 2u;
+            const int k = p / C::CPB, c = (p % C::CPB) ^ swz_b<C::FP8>(k);
+            int col = n0 + C::PE * c;
+            col = col < g.N ? col : g.N - C::PE;
+            b_off[j] = ((uint32_t)k * (uint32_t)g.N + (uint32_t)col) * C::ES;
         }
     }
-    // Loads of k-iteration `kit`.  TAIL: the iteration reaches beyond K (K is a multiple of 8
-    // here); pieces at k >= K are then fetched from a zero piece so that they add nothing.
+    // Loads of k-iteration `kit`.  TAIL: the iteration reaches beyond K (K is a multiple of the
+    // piece length here); pieces at k >= K are then fetched from a zero piece so that they add nothing.
     template <bool TAIL> __device__ __forceinline__ void issue_a(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::A_LD) const {
         const int lane = threadIdx.x % 64;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-        const char* A = static_cast<const char*>(g.A) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * 2));
+        const char* A = static_cast<const char*>(g.A) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * C::ES));
 #pragma unroll
         for (int j = 0; j < C::A_LD; j++) {
             if (j < j0 || j >= j1) continue;
@@ -251,7 +277,7 @@ template <class C> struct DmaMap {
             } else {
                 const int p = (j * C::NW + wave) * 64 + lane;
                 const int r = p / C::CPA, c = (p % C::CPA) ^ swz_a<C::CPA>(r);
-                const char* src = kit * C::BK + 8 * c < g.K ? A + a_off[j] : reinterpret_cast<const char*>(g_zero_piece);
+                const char* src = kit * C::BK + C::PE * c < g.K ? A + a_off[j] : reinterpret_cast<const char*>(g_zero_piece);
                 lds_dma16_ptr(src, lds + (j * C::NW + wave) * 1024);
             }
         }
@@ -259,7 +285,7 @@ template <class C> struct DmaMap {
     template <bool TAIL> __device__ __forceinline__ void issue_b(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::B_LD) const {
         const int lane = threadIdx.x % 64;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-        const char* B = static_cast<const char*>(g.B) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * 2)) * (uint32_t)g.N;
+        const char* B = static_cast<const char*>(g.B) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * C::ES)) * (uint32_t)g.N;
 #pragma unroll
         for (int j = 0; j < C::B_LD; j++) {
             if (j < j0 || j >= j1) continue;
@@ -274,45 +300,71 @@ template <class C> struct DmaMap {
     }
 };
 
-// 4 k-consecutive elements of one B column out of the row-major [k][n] LDS image: the
+// k-consecutive elements of one B column out of the row-major [k][n] LDS image.  16-bit: the
 // transposing read hands lane j of each 16-lane group column j of a 4 x 16 block whose rows are
-// addressed by lanes 4e..4e+3 of the group.
-__device__ __forceinline__ uint2 read_b_transposed(const unsigned char* p) {
+// addressed by lanes 4e..4e+3 of the group (4 k per read).  8-bit: an 8 x 16 block whose rows are
+// addressed by lanes 2e, 2e+1 (8 k per read).
+__device__ __forceinline__ uint2 read_b_tr16(const unsigned char* p) {
     s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
     return __builtin_bit_cast(uint2, v);
+}
+__device__ __forceinline__ i32x2 read_b_tr8(const unsigned char* p) {
+    return __builtin_amdgcn_ds_read_tr8_b64_v2i32((i32x2 __attribute__((address_space(3)))*)(p));
 }
 
 // Lane-constant parts of the operand addresses inside a stage.
 template <class C> struct FragMap {
-    uint32_t a_kk[C::KK];   // byte offset of this lane's A piece for k-step kk, matrix-core block row 0
-    uint32_t b_ni[C::NI];   // byte offset of this lane's B read for block column ni, k-step 0, half 0
+    uint32_t a_kk[C::KK][C::APL];   // byte offsets of this lane's A piece(s) for k-step kk, block row 0
+    uint32_t b_ni[C::NI];           // byte offset of this lane's first B read for block column ni, k-step 0
     __device__ __forceinline__ void init() {
         const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
         const int wm = wave / C::WN, wn = wave % C::WN;
         const int row = wm * C::WTM + lane % C::MF;          // + mi * MF keeps row % 16
 #pragma unroll
         for (int kk = 0; kk < C::KK; kk++)
-            a_kk[kk] = (row * C::CPA + ((kk * C::KG + lane / C::MF) ^ swz_a<C::CPA>(row))) * 16;
-        const int krow = 8 * (lane / C::MF) + (lane % 16) / 4;   // + kk * KM + 4 * half keeps krow % 4
+#pragma unroll
+            for (int i = 0; i < C::APL; i++)
+                a_kk[kk][i] = (row * C::CPA + ((kk * (C::KM / C::PE) + (lane / C::MF) * C::APL + i) ^ swz_a<C::CPA>(row))) * 16;
+        // rows of one transposing read: 4 (16-bit) or 8 (8-bit); later reads and k-steps add multiples of that
+        const int krow = C::KPL * (lane / C::MF) + (C::FP8 ? (lane % 16) / 2 : (lane % 16) / 4);
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++) {
-            const int col = wn * C::WTN + ni * C::MF + 16 * ((lane % C::MF) / 16) + 4 * (lane % 4);
-            b_ni[ni] = (krow * C::CPB + ((col / 8) ^ swz_b(krow))) * 16 + (col % 8) * 2;
+            const int col = wn * C::WTN + ni * C::MF + 16 * ((lane % C::MF) / 16) + (C::FP8 ? 8 * (lane % 2) : 4 * (lane % 4));
+            b_ni[ni] = (krow * C::CPB + ((col / C::PE) ^ swz_b<C::FP8>(krow))) * 16 + (col % C::PE) * C::ES;
         }
     }
 };
 
-template <class C> struct Frags {
+template <class C, bool FP8 = C::FP8> struct Frags;
+template <class C> struct Frags<C, false> {
     uint4 a[C::MI], b[C::NI];
     __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
 #pragma unroll
         for (int mi = 0; mi < C::MI; mi++)
-            a[mi] = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk] + mi * C::MF * C::CPA * 16);
+            a[mi] = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][0] + mi * C::MF * C::CPA * 16);
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++) {
             const unsigned char* p = b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16;
-            const uint2 lo = read_b_transposed(p), hi = read_b_transposed(p + 4 * C::CPB * 16);
+            const uint2 lo = read_b_tr16(p), hi = read_b_tr16(p + 4 * C::CPB * 16);
             b[ni] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+    }
+};
+template <class C> struct Frags<C, true> {
+    i32x8 a[C::MI], b[C::NI];
+    __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; mi++) {
+            const uint4 lo = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][0] + mi * C::MF * C::CPA * 16);
+            const uint4 hi = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][1] + mi * C::MF * C::CPA * 16);
+            a[mi] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        }
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ni++) {
+            const unsigned char* p = b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16;
+            const i32x2 q0 = read_b_tr8(p), q1 = read_b_tr8(p + 8 * C::CPB * 16);
+            const i32x2 q2 = read_b_tr8(p + 16 * C::CPB * 16), q3 = read_b_tr8(p + 24 * C::CPB * 16);
+            b[ni] = i32x8{q0[0], q0[1], q1[0], q1[1], q2[0], q2[1], q3[0], q3[1]};
         }
     }
 };
@@ -632,15 +684,15 @@ typedef void (*kernel_fn)(GemmArgs);
 struct KernelEntry {
     int dtype, bm, bn, bk, variant;
     kernel_fn aligned, generic;
-    int threads, lds_bytes;
+    int threads, lds_bytes, piece_elems;
     std::atomic<int> max_resident{-1};   // co-resident workgroups on the device, -1 = not yet asked
-    KernelEntry(int d, int m, int n, int k, int v, kernel_fn a, kernel_fn g, int t, int l)
-        : dtype(d), bm(m), bn(n), bk(k), variant(v), aligned(a), generic(g), threads(t), lds_bytes(l) {}
+    KernelEntry(int d, int m, int n, int k, int v, kernel_fn a, kernel_fn g, int t, int l, int pe)
+        : dtype(d), bm(m), bn(n), bk(k), variant(v), aligned(a), generic(g), threads(t), lds_bytes(l), piece_elems(pe) {}
 };
 
 template <class C> KernelEntry* make_entry(int variant = 0) {
     return new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, streamk_gemm_kernel<C, true>, streamk_gemm_kernel<C, false>,
-                           C::THREADS, C::LDS_BYTES);
+                           C::THREADS, C::LDS_BYTES, C::PE);
 }
 
 // Tile shapes with a kernel: <dtype, BM, BN, BK, waves along M, waves along N, matrix-core block,
@@ -668,6 +720,10 @@ KernelEntry** kernel_table(int* count) {
     std::call_once(once, [] {
         add_dtype<SK_BF16>(table, &n);
         add_dtype<SK_F16>(table, &n);
+        // 8-bit inputs: same byte footprint per stage as the 16-bit tiles with twice the k
+        table[n++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 4, 32, 3, 2>>();
+        table[n++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 2, 32, 3, 2>>(1);
+        table[n++] = make_entry<Cfg<SK_FP8_E4M3, 128, 256, 128, 2, 4, 32, 3, 3>>();
     });
     *count = n;
     return table;
@@ -738,7 +794,7 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k);
     if (!e) return SK_ERR_UNSUPPORTED;
     if (plan->needs_fixup && !plan->workspace) return SK_ERR_WORKSPACE;
-    const bool aligned = (h.K % 8 == 0) && (h.N % 8 == 0);
+    const bool aligned = (h.K % e->piece_elems == 0) && (h.N % e->piece_elems == 0);   // whole 16-byte pieces per row
     kernel_fn fn = aligned ? e->aligned : e->generic;
 
     if (e->max_resident.load() < 0) {

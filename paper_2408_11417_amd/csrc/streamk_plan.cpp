@@ -67,6 +67,11 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
     // iterations split evenly over the grid plus the cost of exchanging partial tiles, and keeps
     // the cheapest.  Constants (sustained TFLOP/s of each kernel with the grid full, microseconds
     // to drain / store a tile and to park or fetch a partial) were read off timing runs on MI355X.
+    if (in_dtype == SK_FP8_E4M3) {   // two 8-bit tile shapes: the large one unless it leaves most of the grid idle
+        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
+        out_blk[0] = t256 >= 96 ? 256 : 128; out_blk[1] = 256; out_blk[2] = 128;
+        return SK_OK;
+    }
     struct Cand { int bm, bn; double tflops; };
     static const Cand cands[] = {{256, 256, 1150.}, {256, 128, 890.}, {128, 128, 790.}, {64, 128, 570.}, {32, 128, 300.}};
     const int bk = 64, grid = 256;

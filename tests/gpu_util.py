@@ -10,7 +10,7 @@ OUT_TORCH = {sk.SK_F16: torch.int16, sk.SK_BF16: torch.int16, sk.SK_F32: torch.f
 
 def to_device(bits):
     """numpy storage bit patterns (uint16 / uint8) -> device tensor with the same bytes."""
-    view = bits.view(np.int16) if bits.dtype == np.uint16 else bits
+    view = bits.view(np.int16) if bits.dtype == np.uint16 else bits.view(np.uint8)
     return torch.from_numpy(np.ascontiguousarray(view)).cuda()
 
 

@@ -16,7 +16,7 @@ from tests.gpu_util import Runner, to_device
 
 pytestmark = pytest.mark.gpu
 TOL_16, TOL_32 = 1e-2, 1e-4
-ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16}
+ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16, inputs.E4M3: G.E4M3}
 
 
 def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False):
@@ -143,3 +143,35 @@ def test_config5_large_square_bf16_sampled_rows():
     ref = G.gemm_fp64(c["A"], c["B"], G.BF16, rows=rows)
     for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK3_DP, sk.SK_POLICY_ALL_SK):
         _run_and_compare(c["A"], c["B"], inputs.BF16, policy, None, 256, rows=rows, ref=ref)
+
+
+# ---- 8-bit (e4m3) inputs ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("blk", [(256, 256, 128), (128, 256, 128)])
+def test_fp8_integer_inputs_bit_exact(blk):
+    M, N, K = 2 * blk[0] + 40, 2 * blk[1] + 80, 3 * blk[2] + 48
+    A, B = inputs.small_int_pair(M, N, K, inputs.E4M3, 31)
+    ref = G.gemm_fp64(A, B, G.E4M3)
+    for policy in range(8):
+        _run_and_compare(A, B, inputs.E4M3, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True)
+    # unaligned K and N take the element-wise guarded path
+    A, B = inputs.small_int_pair(70, 300, 203, inputs.E4M3, 32)
+    ref = G.gemm_fp64(A, B, G.E4M3)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(A, B, inputs.E4M3, policy, blk, grid=16, out_dtype=sk.SK_F32, ref=ref, exact=True)
+
+
+def test_fp8_uniform_inputs_medium():
+    A, B = inputs.uniform_pair(520, 776, 1040, inputs.E4M3, 33)
+    ref = G.gemm_fp64(A, B, G.E4M3)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(A, B, inputs.E4M3, policy, None, 256, ref=ref)                       # bf16 output
+        _run_and_compare(A, B, inputs.E4M3, policy, None, 256, out_dtype=sk.SK_F32, ref=ref)
+
+
+def test_config5_large_square_fp8_sampled_rows():
+    c = inputs.config5(inputs.E4M3)
+    rows = inputs.sample_rows(c["M"], 24, 6)
+    ref = G.gemm_fp64(c["A"], c["B"], G.E4M3, rows=rows)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK3_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(c["A"], c["B"], inputs.E4M3, policy, None, 256, rows=rows, ref=ref)
