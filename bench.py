@@ -16,6 +16,9 @@ import time
 
 import numpy as np
 
+# HBM bytes per launch of the data-parallel policy on the default workload, from rocprofv3
+# FETCH_SIZE / WRITE_SIZE scaled by a plain-copy calibration (profiles/streamk_gemm_kernel_cfg2_bf16_3840x4224x4096.txt)
+MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.4e6 + 32.4e6}
 PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "e4m3": 5033.2}    # dense MFMA peak of MI355X
 
 
@@ -141,7 +144,9 @@ def main():
         "config": {"workload": c["label"], "M": M, "N": N, "K": K,
                    "tile": [info["blk_m"], info["blk_n"], info["blk_k"]], "grid": info["grid"]},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                     "frac": round(achieved / peak, 4), "traffic": None,
+                     "frac": round(achieved / peak, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, sk.POLICY_NAMES[sel])),
+                     "algorithmic_bytes": (M * K + K * N) * (1 if dt == 2 else 2) + M * N * 2,
                      "kernel": "streamk_gemm_kernel", "kernel_ms": round(kernel_ms, 5)},
         "selected_policy": sk.POLICY_NAMES[sel],
         "selected_over_best": round(best / t_pol[sel], 4),

@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 #include <atomic>
 #include <cstdlib>
+#include <type_traits>
 #include <mutex>
 #include "streamk_internal.h"
 
@@ -162,9 +163,6 @@ __device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
 // lds_base + 16 * l; lds_base must be wave-uniform.  Completion is tracked by vmcnt only; the
 // compiler is not told that LDS is written: the caller orders the reads with s_waitcnt + barrier.
 __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_base) {
-#ifdef SK_EXP_NO_DMA
-    return;
-#endif
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base));
 }
 __device__ __forceinline__ void lds_dma16_ptr(const void* gptr, uint32_t lds_base) {
@@ -369,38 +367,6 @@ template <class C> struct Frags<C, true> {
     }
 };
 
-struct NoIssue {
-    __device__ __forceinline__ void operator()(int) const {}
-};
-
-// All k-steps of one stage: the operands of step kk+1 are read from LDS while the matrix cores
-// work on step kk.  issue(kk) is called once per k-step: the caller spreads the global->LDS
-// requests of a later stage over the steps, so that no wave sits in a burst of memory
-// instructions while the matrix cores idle.
-template <class C, class Issue>
-__device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm,
-                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI], const Issue& issue) {
-#ifdef SK_EXP_NO_COMPUTE
-    return;
-#endif
-    Frags<C> f[2];
-    f[0].load(a_stage, b_stage, fm, 0);
-#pragma unroll
-    for (int kk = 0; kk < C::KK; kk++) {
-        if (kk + 1 < C::KK) f[(kk + 1) & 1].load(a_stage, b_stage, fm, kk + 1);
-        issue(kk);
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ni++)
-#ifdef SK_EXP_NO_MFMA
-                acc[mi][ni][0] += __uint_as_float(f[kk & 1].a[mi].x ^ f[kk & 1].b[ni].y);
-#else
-                acc[mi][ni] = Mfma<C::DT, C::MF>::run(f[kk & 1].a[mi], f[kk & 1].b[ni], acc[mi][ni]);
-#endif
-    }
-}
-
 __device__ __forceinline__ u16 to_bf16_bits(float f) {
     uint32_t u = __builtin_bit_cast(uint32_t, f);
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u16)((u >> 16) | 0x40);   // quiet NaN
@@ -408,83 +374,106 @@ __device__ __forceinline__ u16 to_bf16_bits(float f) {
 }
 
 template <class C, int LATER> __device__ __forceinline__ void wait_stage(int later) {
-    // wait until the loads of the current iteration have landed, given how many iterations follow
+    // wait until the loads of the wanted stage have landed, given how many stages follow it
     if (LATER == 0 || later >= LATER) wait_vmcnt<C::in_flight(LATER)>();
     else wait_stage<C, (LATER > 0 ? LATER - 1 : 0)>(later);
 }
 
+// The matrix-core work of one k-step.
+template <class C>
+__device__ __forceinline__ void mma_step(const Frags<C>& f, typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ni++)
+            acc[mi][ni] = Mfma<C::DT, C::MF>::run(f.a[mi], f.b[ni], acc[mi][ni]);
+}
+
+// All k-steps of one stage, for the register-staged path: the operands of step kk+1 are read from
+// LDS while the matrix cores work on step kk.
+template <class C>
+__device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm,
+                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+    Frags<C> f[2];
+    f[0].load(a_stage, b_stage, fm, 0);
+#pragma unroll
+    for (int kk = 0; kk < C::KK; kk++) {
+        if (kk + 1 < C::KK) f[(kk + 1) & 1].load(a_stage, b_stage, fm, kk + 1);
+        mma_step<C>(f[kk & 1], acc);
+    }
+}
+
 // MAC loop of one segment (Algorithm 1, line 13): k-iterations [k_begin, k_end) of one tile.
+//
+// Software pipeline of the LDS-DMA path.  Stage s (one k-iteration) lives in A ring slot s % NSA and
+// B ring slot s % NSB.  The barrier that hands stage i+1 to the waves sits one k-step *before* the
+// end of stage i: by then every wave has read the operands of stage i's last k-step into registers,
+// so (1) stage i's slots can be refilled at once (with stages i+NSB / i+NSA), (2) the operands of
+// stage i+1's first k-step are read while the matrix cores still work on stage i's last one, and
+// (3) the time a wave spends at the barrier is covered by matrix-core work already queued.
 template <class C, bool ALIGNED>
 __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int k_begin, int k_end,
                                          unsigned char* smem, const FragMap<C>& fm,
-#ifdef SK_EXP_CLOCK
-                                         unsigned long long (&exp_t)[4],
-#endif
                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     const int nk = k_end - k_begin;
     if (C::DIRECT && ALIGNED) {
-        // A tile of iteration i sits in A ring slot i % NSA, its B tile in B ring slot i % NSB; in
-        // iteration i the B tile of iteration i+NSB-1 and then the A tile of iteration i+NSA-1 are requested
+        static_assert(!C::DIRECT || C::KK % 2 == 0, "operand double buffering assumes an even number of k-steps");
         const uint32_t lds0 = (uint32_t)(size_t)(lds_byte*)smem;
         const int full_k = g.K / C::BK;             // iterations below this index are entirely inside K
         DmaMap<C> dm;
         dm.init(g, m0, n0);
+        // request batch j (issued after the barrier of stage j): B tile of stage j+NSB, then A tile of
+        // stage j+NSA, into the slots of stage j; step / steps select a slice of the batch
+        auto issue_batch = [&](int j, int slot_a, int slot_b, int step, int steps) {
+            const int ib = j + C::NSB, ia = j + C::NSA;
+            const int q0 = step * C::LPS / steps, q1 = (step + 1) * C::LPS / steps;
+            const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
+            const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
+            if (ib >= 0 && ib < nk && b1 > b0) {
+                const uint32_t lds = lds0 + C::B_RING + slot_b * C::B_BYTES;
+                if (k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
+                else dm.template issue_b<true>(g, k_begin + ib, lds, b0, b1);
+            }
+            if (ia >= 0 && ia < nk && a1 > a0) {
+                const uint32_t lds = lds0 + slot_a * C::A_BYTES;
+                if (k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds, a0, a1);
+                else dm.template issue_a<true>(g, k_begin + ia, lds, a0, a1);
+            }
+        };
+        // the batches that stages before the first would have requested, all but the last
 #pragma unroll
-        for (int j = 1 - C::NSA; j < 0; j++) {       // the requests that iterations before the first would have made
-            const int ib = j + C::NSB - 1, ia = j + C::NSA - 1;
-            if (ib >= 0 && ib < nk) {
-                if (k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds0 + C::B_RING + ib * C::B_BYTES);
-                else dm.template issue_b<true>(g, k_begin + ib, lds0 + C::B_RING + ib * C::B_BYTES);
+        for (int j = -C::NSA; j <= -2; j++)
+            issue_batch(j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
+        Frags<C> f[2];
+        int ca = C::NSA - 1, cb = C::NSB - 1;        // ring slots of stage i (i = -1: the slots batch -1 fills)
+        // one trip = [barrier that hands over stage i+1] [requests of batch i, sliced over the k-steps]
+        //            [last k-step of stage i] [k-steps 0 .. KK-2 of stage i+1]; FIRST: i = -1, no stage i yet
+        auto trip = [&](int i, auto first) {
+            constexpr bool FIRST = decltype(first)::value;
+            const bool has_next = i + 1 < nk;
+            const int na = ca + 1 == C::NSA ? 0 : ca + 1, nb = cb + 1 == C::NSB ? 0 : cb + 1;   // slots of stage i+1
+            const unsigned char* a_next = smem + na * C::A_BYTES;
+            const unsigned char* b_next = smem + C::B_RING + nb * C::B_BYTES;
+            if (has_next) {
+                wait_stage<C, C::NSA - 1>(nk - 2 - i);   // stage i+1 has landed (this wave's share)
+                __syncthreads();                         // ... and everybody's; stage i's slots are free
+                f[0].load(a_next, b_next, fm, 0);
             }
-            if (ia >= 0 && ia < nk) {
-                if (k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds0 + ia * C::A_BYTES);
-                else dm.template issue_a<true>(g, k_begin + ia, lds0 + ia * C::A_BYTES);
+            issue_batch(i, ca, cb, 0, C::KK);
+            if (!FIRST) mma_step<C>(f[1], acc);          // last k-step of stage i
+            if (has_next) {
+#pragma unroll
+                for (int kk = 0; kk < C::KK - 1; kk++) {
+                    f[(kk + 1) & 1].load(a_next, b_next, fm, kk + 1);
+                    issue_batch(i, ca, cb, kk + 1, C::KK);
+                    mma_step<C>(f[kk & 1], acc);
+                }
             }
-        }
-        int sa = 0, sb = 0, fa = C::NSA - 1, fb = C::NSB - 1;   // ring slots: current A / B, A / B to refill
-        for (int i = 0; i < nk; i++) {
-#ifdef SK_EXP_CLOCK
-            const unsigned long long t0 = __builtin_readcyclecounter();
-#endif
-            wait_stage<C, C::NSA - 1>(nk - 1 - i);
-#ifdef SK_EXP_CLOCK
-            const unsigned long long t1 = __builtin_readcyclecounter();
-#endif
-            __syncthreads();
-#ifdef SK_EXP_CLOCK
-            const unsigned long long t2 = __builtin_readcyclecounter();
-#endif
-            const int ib = i + C::NSB - 1, ia = i + C::NSA - 1;
-            const bool do_b = ib < nk, do_a = ia < nk;
-            const bool tail_b = k_begin + ib >= full_k, tail_a = k_begin + ia >= full_k;
-            const uint32_t lds_b = lds0 + C::B_RING + fb * C::B_BYTES, lds_a = lds0 + fa * C::A_BYTES;
-            // request q of this iteration: the B_LD loads of the B tile first, then the A_LD loads of the A tile
-            auto issue = [&](int kk) {
-                const int q0 = kk * C::LPS / C::KK, q1 = (kk + 1) * C::LPS / C::KK;
-                const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
-                const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
-                if (do_b && b1 > b0) {
-                    if (!tail_b) dm.template issue_b<false>(g, k_begin + ib, lds_b, b0, b1);
-                    else dm.template issue_b<true>(g, k_begin + ib, lds_b, b0, b1);
-                }
-                if (do_a && a1 > a0) {
-                    if (!tail_a) dm.template issue_a<false>(g, k_begin + ia, lds_a, a0, a1);
-                    else dm.template issue_a<true>(g, k_begin + ia, lds_a, a0, a1);
-                }
-            };
-#ifdef SK_EXP_CLOCK
-            const unsigned long long t3 = __builtin_readcyclecounter();
-#endif
-            mac_stage<C>(smem + sa * C::A_BYTES, smem + C::B_RING + sb * C::B_BYTES, fm, acc, issue);
-#ifdef SK_EXP_CLOCK
-            const unsigned long long t4 = __builtin_readcyclecounter();
-            exp_t[0] += t1 - t0; exp_t[1] += t2 - t1; exp_t[2] += t3 - t2; exp_t[3] += t4 - t3;
-#endif
-            sa = sa + 1 == C::NSA ? 0 : sa + 1;
-            fa = fa + 1 == C::NSA ? 0 : fa + 1;
-            sb = sb + 1 == C::NSB ? 0 : sb + 1;
-            fb = fb + 1 == C::NSB ? 0 : fb + 1;
-        }
+            ca = na;
+            cb = nb;
+        };
+        trip(-1, std::true_type());
+        for (int i = 0; i < nk; i++) trip(i, std::false_type());
         __syncthreads();                             // all reads done before the next segment refills
     } else {
         for (int k = k_begin; k < k_end; k++) {
@@ -493,7 +482,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
             unsigned char* b_stage = smem + C::B_RING + slot * C::B_BYTES;
             fill_stage_staged<C, ALIGNED>(g, m0, n0, k, a_stage, b_stage);
             __syncthreads();
-            mac_stage<C>(a_stage, b_stage, fm, acc, NoIssue());
+            mac_stage<C>(a_stage, b_stage, fm, acc);
         }
         __syncthreads();
     }
@@ -547,10 +536,6 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     const int x = logical_wg(blockIdx.x, g.grid);
     FragMap<C> fm;
     fm.init();
-#ifdef SK_EXP_CLOCK
-    const unsigned long long exp_c0 = __builtin_readcyclecounter(), exp_r0 = __builtin_amdgcn_s_memrealtime();
-    unsigned long long exp_t[4] = {0, 0, 0, 0};
-#endif
 
     // Algorithm 1, lines 5-6 (clamped): this workgroup's share of the Stream-K iterations
     int it = x * g.ipw, it_end = it + g.ipw;
@@ -585,9 +570,6 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             tn = (int)(within / rows);
             tm = (int)band * SK_GROUP_ROWS + (int)(within - (uint32_t)tn * rows);
         }
-#ifdef SK_EXP_SAME_TILE
-        tm = tn = 0;
-#endif
         const int m0 = tm * C::BM, n0 = tn * C::BN;
 
         Acc acc[C::MI][C::NI];
@@ -595,11 +577,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
             for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
-#ifdef SK_EXP_CLOCK
-        mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, exp_t, acc);
-#else
         mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, acc);
-#endif
 
         // ---- fix-up
         // (the empty asm statements keep the per-block addresses from being computed once, ahead
@@ -666,17 +644,6 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             else reduce_and_store<C, SK_F32, false>(g, row0, col0, part0, n_contrib, acc);
         }
     }
-#ifdef SK_EXP_CLOCK
-    if (x == 0 && tid == 0 && g.status) {
-        unsigned long long* dbg = reinterpret_cast<unsigned long long*>(g.status) + 1;
-        dbg[0] = __builtin_readcyclecounter() - exp_c0;
-        dbg[1] = __builtin_amdgcn_s_memrealtime() - exp_r0;
-    }
-    if (x == 0 && lane == 0 && g.status) {
-        unsigned long long* dbg = reinterpret_cast<unsigned long long*>(g.status) + 3 + wave * 4;
-        for (int q = 0; q < 4; q++) dbg[q] = exp_t[q];
-    }
-#endif
 }
 
 // ---- host side ---------------------------------------------------------------------------------

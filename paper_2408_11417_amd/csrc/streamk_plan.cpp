@@ -109,8 +109,8 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
     if (!dtype_in_ok(in_dtype)) return SK_ERR_INVALID_ARG;
     const int out_dtype = c.out_dtype ? c.out_dtype - 1 : (in_dtype == SK_FP8_E4M3 ? SK_BF16 : in_dtype);
     if (!dtype_out_ok(out_dtype)) return SK_ERR_INVALID_ARG;
-    const int order = c.tile_order ? c.tile_order - 1 : SK_ORDER_GROUPED;
-    if (order != SK_ORDER_ROW_MAJOR && order != SK_ORDER_GROUPED) return SK_ERR_INVALID_ARG;
+    int order = c.tile_order ? c.tile_order - 1 : -1;   // -1: decided below, once the split is known
+    if (order != -1 && order != SK_ORDER_ROW_MAJOR && order != SK_ORDER_GROUPED) return SK_ERR_INVALID_ARG;
     int32_t blk[3] = {c.blk_m, c.blk_n, c.blk_k};
     if (!blk[0] || !blk[1] || !blk[2]) {
         int32_t def[3];
@@ -122,7 +122,7 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
     sk_plan_header h{};
     h.M = M; h.N = N; h.K = K; h.policy = policy;
     h.blk_m = blk[0]; h.blk_n = blk[1]; h.blk_k = blk[2]; h.grid = grid;
-    h.in_dtype = in_dtype; h.out_dtype = out_dtype; h.tile_order = order;
+    h.in_dtype = in_dtype; h.out_dtype = out_dtype;
     // Algorithm 1, lines 2-3
     const int64_t tiles_m = ceil_div(M, blk[0]), tiles_n = ceil_div(N, blk[1]);
     const int64_t ipt = ceil_div(K, blk[2]);
@@ -142,6 +142,11 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
         sk_tiles = tiles % grid + (int64_t)(b - 1) * grid;
         if (sk_tiles > tiles) sk_tiles = tiles;
     }
+    // Default tile order: workgroups of a pure Stream-K schedule sit at different k offsets of
+    // neighbouring tiles, where the row-major order measured faster; schedules with whole-tile
+    // (data-parallel) work gain from the compact blocks of the grouped order.
+    if (order < 0) order = (sk_tiles == tiles) ? SK_ORDER_ROW_MAJOR : SK_ORDER_GROUPED;
+    h.tile_order = order;
     h.sk_tiles = (int32_t)sk_tiles;
     h.dp_tiles = (int32_t)(tiles - sk_tiles);
     h.sk_iters = sk_tiles * ipt;

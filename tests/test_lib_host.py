@@ -73,6 +73,9 @@ def test_plan_defaults_and_errors():
     info = sk.sk_plan_info(p)
     assert (info["grid"], info["in_dtype"], info["out_dtype"]) == (256, sk.SK_BF16, sk.SK_BF16)
     assert info["tile_order"] == sk.SK_ORDER_GROUPED
+    q = sk.sk_plan(8192, 8192, 8192, sk.SK_POLICY_ALL_SK)
+    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_ROW_MAJOR      # pure Stream-K schedules default to row-major
+    sk.sk_plan_destroy(q)
     with pytest.raises(sk.StreamKError):
         sk.sk_plan_tile_coords(p, info["tiles"])
     assert (info["blk_m"], info["blk_n"], info["blk_k"]) == sk.sk_default_tile(8192, 8192, 8192)
