@@ -1,22 +1,26 @@
-"""Build libstreamk.so (host planner + Bloom selector + gfx950 kernels) in-tree with hipcc."""
+"""Build libstreamk.so (host planner + Bloom selector + gfx950 kernels) in-tree with hipcc.
+
+Every source is compiled to an object for gfx950 (the kernel translation units in parallel), then
+linked into one shared library next to this file.
+"""
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstreamk.so")
-SOURCES = ["streamk_plan.cpp", "streamk_bloom.cpp", "streamk_gemm.hip"]
+SOURCES = ["streamk_plan.cpp", "streamk_bloom.cpp", "streamk_gemm.hip",
+           "streamk_gemm_bf16.hip", "streamk_gemm_f16.hip", "streamk_gemm_fp8.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose=False, extra_flags=()):
-    """Compile every source for gfx950 and link the shared library next to this file."""
-    cmd = [HIPCC] + FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -25,6 +29,18 @@ def build_library(verbose=False, extra_flags=()):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build_library(verbose=False, extra_flags=()):
+    """Compile every source for gfx950 and link the shared library next to this file."""
+    os.makedirs(OBJ, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objs = [os.path.join(OBJ, s.rsplit(".", 1)[0] + ".o") for s in SOURCES]
+    cmds = [[HIPCC] + FLAGS + list(extra_flags) + inc + ["-c", os.path.join(CSRC, s), "-o", o]
+            for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(cmds), int(os.environ.get("MAX_JOBS", "6")))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
     return LIB
 
 

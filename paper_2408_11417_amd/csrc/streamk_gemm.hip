@@ -1,696 +1,20 @@
-// Stream-K GEMM for gfx950 (MI355X): one persistent kernel serves every
-// scheduling policy.  Each workgroup derives its own share of the iteration
-// space from a handful of plan numbers (Algorithm 1, lines 4-12), runs the MAC
-// loop of each segment on the matrix cores, and either stores the tile, parks an
-// fp32 partial in the workspace, or - as the tile's owner - waits for the parked
-// partials and adds them in a fixed order (the synchronised reduction that
-// Sec. 5.3 names as the alternative to Algorithm 1's atomic adds).
-//
-// MAC loop data path: A (row-major, k contiguous) and B (row-major, n contiguous)
-// tiles go from global memory straight into LDS with 16-byte LDS-DMA loads, into
-// a ring of NS stages; the LDS image is XOR-swizzled at 16-byte granularity (the
-// swizzle is applied by choosing which global piece each lane fetches) so that
-// the matrix-core operand reads are bank-conflict free without padding.  A
-// operands are read with 16-byte LDS reads, B operands with the transposing
-// 8-byte reads that turn the [k][n] image into k-contiguous lanes.
-#include <hip/hip_runtime.h>
-#include <atomic>
+// Host side of the Stream-K GEMM: kernel table, workspace handling and the sk_gemm launcher.
 #include <cstdlib>
-#include <type_traits>
 #include <mutex>
-#include "streamk_internal.h"
+#include "streamk_kernels.h"
+
+using namespace streamk_detail;
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef int i32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x8 __attribute__((ext_vector_type(8)));
-typedef unsigned short u16;
-typedef __attribute__((address_space(3))) unsigned char lds_byte;
-
-struct GemmArgs {
-    const void* A;
-    const void* B;
-    void* D;
-    float* partials;       // grid slots of BM*BN floats
-    uint32_t* flags;       // one per workgroup, SK_FLAG_STRIDE bytes apart
-    uint32_t* status;      // set non-zero when an owner gives up waiting
-    int M, N, K;
-    int tiles_m, tiles_n, tiles, ipt, sk_tiles, ipw, grid, sk_iters, tile_order;
-    uint32_t epoch, spin_limit;
-    int out_dtype;
-};
-
-// ---- matrix-core wrappers ---------------------------------------------------------------------
-// One instruction multiplies an MF x KM block of A by a KM x MF block of B.  Lane l holds, for A,
-// row l % MF and the 8 consecutive k starting at 8 * (l / MF); for B, column l % MF and the same
-// k; for the MF x MF result, column l % MF and rows (r/4) * (256/MF) + 4 * (l / MF) + r % 4.
-template <int DT, int MF> struct Mfma;
-template <> struct Mfma<SK_BF16, 32> {
-    typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Mfma<SK_F16, 32> {
-    typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Mfma<SK_BF16, 16> {
-    typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Mfma<SK_F16, 16> {
-    typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-};
-
-// fp8 (e4m3): the scaled 8-bit instruction with both block scales at 2^0 (biased exponent 127);
-// per lane 32 consecutive k (8 registers) of row / column l % MF starting at 32 * (l / MF).
-template <> struct Mfma<SK_FP8_E4M3, 32> {
-    typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(i32x8 a, i32x8 b, Acc c) {
-        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
-    }
-};
-template <> struct Mfma<SK_FP8_E4M3, 16> {
-    typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(i32x8 a, i32x8 b, Acc c) {
-        return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
-    }
-};
-
-template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MF_, int NSA_, int NSB_ = NSA_>
-struct Cfg {
-    static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MF = MF_;
-    static constexpr int NSA = NSA_, NSB = NSB_;        // LDS ring depth of the A and of the B tiles
-    static constexpr int NW = WM * WN, THREADS = 64 * NW;
-    static constexpr int WTM = BM / WM, WTN = BN / WN;   // tile of one wave
-    static constexpr int MI = WTM / MF, NI = WTN / MF;   // matrix-core blocks per wave tile
-    static constexpr bool FP8 = DT == SK_FP8_E4M3;
-    static constexpr int ES = FP8 ? 1 : 2;               // bytes per input element
-    static constexpr int PE = 16 / ES;                   // elements per 16-byte piece
-    static constexpr int KPL = FP8 ? 32 : 8;             // consecutive k per lane per instruction
-    static constexpr int APL = KPL / PE;                 // A pieces per lane per instruction
-    static constexpr int KG = 64 / MF;                   // groups of KPL k across the lanes
-    static constexpr int KM = KPL * KG;                  // k per instruction
-    static constexpr int KK = BK / KM;
-    static constexpr int ACC = MF * MF / 64;             // accumulator registers per block
-    // LDS: a ring of NSA A tiles (BM rows of CPA 16-byte pieces) followed by a ring of NSB B tiles
-    // (BK rows of CPB pieces), no padding.  A may be one stage deeper than B: its loads then run
-    // two iterations ahead and only the B tile has to arrive within one iteration.
-    static constexpr int CPA = BK / PE, CPB = BN / PE;
-    static constexpr int A_PIECES = BM * CPA, B_PIECES = BK * CPB;
-    static constexpr int A_BYTES = A_PIECES * 16, B_BYTES = B_PIECES * 16;
-    static constexpr int B_RING = NSA * A_BYTES;         // byte offset of the B ring
-    static constexpr int LDS_BYTES = NSA * A_BYTES + NSB * B_BYTES;
-    // one LDS-DMA instruction of one wave fills 64 consecutive pieces
-    static constexpr bool DIRECT = (A_PIECES % (64 * NW) == 0) && (B_PIECES % (64 * NW) == 0);
-    static constexpr int A_LD = A_PIECES / (64 * NW), B_LD = B_PIECES / (64 * NW);
-    static constexpr int LPS = A_LD + B_LD;              // LDS-DMA loads per stage per wave
-    // register-staged fill (unaligned problems, tiles too small for the DMA split)
-    static constexpr int CA = (A_PIECES + THREADS - 1) / THREADS, CB = (B_PIECES + THREADS - 1) / THREADS;
-    static_assert(WTM % MF == 0 && WTN % MF == 0 && BK % KM == 0, "tile does not divide");
-    static_assert(CPA == 4 || CPA == 8 || CPA == 16, "A swizzle assumes 64/128/256-byte rows");
-    static_assert(CPB >= 16, "B swizzle assumes rows of at least 256 bytes");
-    static_assert(NSB >= 2 && (NSA == NSB || NSA == NSB + 1) && LDS_BYTES <= 160 * 1024, "LDS budget / ring depths");
-    static_assert((NSA - 1) * LPS <= 63, "vmcnt range");
-    // LDS-DMA loads that may still be in flight when iteration i starts, if `later` more
-    // iterations follow it.  Issue order inside an iteration: B tile of iteration +NSB-1, then A
-    // tile of iteration +NSA-1; loads complete in order.
-    static constexpr int in_flight(int later) {
-        int n = 0;
-        if (NSA == NSB) {
-            for (int d = 1; d <= NSA - 2; d++) n += later >= d ? LPS : 0;
-        } else {
-            n += later >= 1 ? A_LD : 0;
-            for (int d = 1; d <= NSB - 2; d++) n += (later >= d ? B_LD : 0) + (later >= d + 1 ? A_LD : 0);
-        }
-        return n;
-    }
-};
-
-// ---- LDS image --------------------------------------------------------------------------------
-// A: piece c of row r sits at position c ^ swz_a(r).  Eight consecutive rows and also sixteen
-// consecutive rows then spread the same logical piece over all banks (32- or 64-bank view).
-template <int CPA> __device__ __forceinline__ int swz_a(int r) {
-    if (CPA == 4) return (r >> 1) & 3;
-    return (r & 7) ^ ((r >> 3) & 1);
-}
-// B: piece c of row k sits at position c ^ swz_b<C::FP8>(k): rows k..k+3, read together by one transposing
-// read, land on different 32-byte and different 64-byte bank groups.
-// (8-bit elements: one transposing read covers 8 rows; rows k..k+7 go to 8 different 32-byte groups.)
-template <bool FP8> __device__ __forceinline__ int swz_b(int k) {
-    if (FP8) return (k & 7) << 1;
-    const int k0 = k & 1, k1 = (k >> 1) & 1;
-    return (k0 << 1) | (k1 << 2) | (k0 << 3);
-}
-
-// Source of the pieces that lie beyond K in a ragged last k-iteration.
-__device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
-
-// 16 bytes global -> LDS without passing through registers.  The LDS destination of lane l is
-// lds_base + 16 * l; lds_base must be wave-uniform.  Completion is tracked by vmcnt only; the
-// compiler is not told that LDS is written: the caller orders the reads with s_waitcnt + barrier.
-__device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base));
-}
-__device__ __forceinline__ void lds_dma16_ptr(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base));
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N <= 63, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);   // lgkmcnt / expcnt not waited
-}
-
-// Hardware workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous block of
-// logical workgroup ids so that neighbours in the schedule (which share tiles and A row-blocks)
-// share an L2.
-__device__ __forceinline__ int logical_wg(int hw, int grid) {
-    return (grid % 8 == 0) ? (hw % 8) * (grid / 8) + hw / 8 : hw;
-}
-
-template <int ES, bool ALIGNED>
-__device__ __forceinline__ uint4 load_piece(const unsigned char* __restrict__ base, int row, int col, int rows, int cols) {
-    // 16 bytes = 16 / ES consecutive elements of a row-major matrix with `cols` columns, zero beyond its edges
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row < rows) {
-        const unsigned char* p = base + (size_t)((uint32_t)row * (uint32_t)cols + (uint32_t)col) * ES;
-        if (ALIGNED) {
-            if (col < cols) v = *reinterpret_cast<const uint4*>(p);
-        } else {
-            unsigned char e[16];
-#pragma unroll
-            for (int i = 0; i < 16; i++) e[i] = (col + i / ES < cols) ? p[i] : (unsigned char)0;
-            v.x = e[0] | (uint32_t)e[1] << 8 | (uint32_t)e[2] << 16 | (uint32_t)e[3] << 24;
-            v.y = e[4] | (uint32_t)e[5] << 8 | (uint32_t)e[6] << 16 | (uint32_t)e[7] << 24;
-            v.z = e[8] | (uint32_t)e[9] << 8 | (uint32_t)e[10] << 16 | (uint32_t)e[11] << 24;
-            v.w = e[12] | (uint32_t)e[13] << 8 | (uint32_t)e[14] << 16 | (uint32_t)e[15] << 24;
-        }
-    }
-    return v;
-}
-
-// Register-staged fill of one stage with zero fill at every edge (same LDS image as the DMA path).
-template <class C, bool ALIGNED>
-__device__ __forceinline__ void fill_stage_staged(const GemmArgs& g, int m0, int n0, int kit, unsigned char* a_stage, unsigned char* b_stage) {
-    const int tid = threadIdx.x;
-    const unsigned char* A = static_cast<const unsigned char*>(g.A);
-    const unsigned char* B = static_cast<const unsigned char*>(g.B);
-    const int k0 = kit * C::BK;
-    uint4 ra[C::CA], rb[C::CB];
-#pragma unroll
-    for (int i = 0; i < C::CA; i++) {
-        const int p = tid + i * C::THREADS;
-        if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES)
-            ra[i] = load_piece<C::ES, ALIGNED>(A, m0 + p / C::CPA, k0 + (p % C::CPA) * C::PE, g.M, g.K);
-    }
-#pragma unroll
-    for (int i = 0; i < C::CB; i++) {
-        const int p = tid + i * C::THREADS;
-        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES)
-            rb[i] = load_piece<C::ES, ALIGNED>(B, k0 + p / C::CPB, n0 + (p % C::CPB) * C::PE, g.K, g.N);
-    }
-    uint4* sA = reinterpret_cast<uint4*>(a_stage);
-    uint4* sB = reinterpret_cast<uint4*>(b_stage);
-#pragma unroll
-    for (int i = 0; i < C::CA; i++) {
-        const int p = tid + i * C::THREADS, r = p / C::CPA;
-        if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES) sA[r * C::CPA + ((p % C::CPA) ^ swz_a<C::CPA>(r))] = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < C::CB; i++) {
-        const int p = tid + i * C::THREADS, k = p / C::CPB;
-        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES) sB[k * C::CPB + ((p % C::CPB) ^ swz_b<C::FP8>(k))] = rb[i];
-    }
-}
-
-// Per-tile addressing of the LDS-DMA loads: lane l of this wave's j-th A instruction fills A
-// position (j * NW + wave) * 64 + l.  Rows beyond M and columns beyond N are clamped to the last
-// valid one: they only feed output elements that are never stored.
-template <class C> struct DmaMap {
-    uint32_t a_off[C::A_LD > 0 ? C::A_LD : 1];   // byte offsets from A / B at k-iteration 0
-    uint32_t b_off[C::B_LD > 0 ? C::B_LD : 1];
-    __device__ __forceinline__ void init(const GemmArgs& g, int m0, int n0) {
-        const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
-#pragma unroll
-        for (int j = 0; j < C::A_LD; j++) {
-            const int p = (j * C::NW + wave) * 64 + lane;
-            const int r = p / C::CPA, c = (p % C::CPA) ^ swz_a<C::CPA>(r);
-            int row = m0 + r;
-            row = row < g.M ? row : g.M - 1;
-            a_off[j] = ((uint32_t)row * (uint32_t)g.K + (uint32_t)(C::PE * c)) * C::ES;
-        }
-#pragma unroll
-        for (int j = 0; j < C::B_LD; j++) {
-            const int p = (j * C::NW + wave) * 64 + lane;
-            const int k = p / C::CPB, c = (p % C::CPB) ^ swz_b<C::FP8>(k);
-            int col = n0 + C::PE * c;
-            col = col < g.N ? col : g.N - C::PE;
-            b_off[j] = ((uint32_t)k * (uint32_t)g.N + (uint32_t)col) * C::ES;
-        }
-    }
-    // Loads of k-iteration `kit`.  TAIL: the iteration reaches beyond K (K is a multiple of the
-    // piece length here); pieces at k >= K are then fetched from a zero piece so that they add nothing.
-    template <bool TAIL> __device__ __forceinline__ void issue_a(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::A_LD) const {
-        const int lane = threadIdx.x % 64;
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-        const char* A = static_cast<const char*>(g.A) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * C::ES));
-#pragma unroll
-        for (int j = 0; j < C::A_LD; j++) {
-            if (j < j0 || j >= j1) continue;
-            if (!TAIL) {
-                lds_dma16(A, a_off[j], lds + (j * C::NW + wave) * 1024);
-            } else {
-                const int p = (j * C::NW + wave) * 64 + lane;
-                const int r = p / C::CPA, c = (p % C::CPA) ^ swz_a<C::CPA>(r);
-                const char* src = kit * C::BK + C::PE * c < g.K ? A + a_off[j] : reinterpret_cast<const char*>(g_zero_piece);
-                lds_dma16_ptr(src, lds + (j * C::NW + wave) * 1024);
-            }
-        }
-    }
-    template <bool TAIL> __device__ __forceinline__ void issue_b(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::B_LD) const {
-        const int lane = threadIdx.x % 64;
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-        const char* B = static_cast<const char*>(g.B) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * C::ES)) * (uint32_t)g.N;
-#pragma unroll
-        for (int j = 0; j < C::B_LD; j++) {
-            if (j < j0 || j >= j1) continue;
-            if (!TAIL) {
-                lds_dma16(B, b_off[j], lds + (j * C::NW + wave) * 1024);
-            } else {
-                const int p = (j * C::NW + wave) * 64 + lane;
-                const char* src = kit * C::BK + p / C::CPB < g.K ? B + b_off[j] : reinterpret_cast<const char*>(g_zero_piece);
-                lds_dma16_ptr(src, lds + (j * C::NW + wave) * 1024);
-            }
-        }
-    }
-};
-
-// k-consecutive elements of one B column out of the row-major [k][n] LDS image.  16-bit: the
-// transposing read hands lane j of each 16-lane group column j of a 4 x 16 block whose rows are
-// addressed by lanes 4e..4e+3 of the group (4 k per read).  8-bit: an 8 x 16 block whose rows are
-// addressed by lanes 2e, 2e+1 (8 k per read).
-__device__ __forceinline__ uint2 read_b_tr16(const unsigned char* p) {
-    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
-    return __builtin_bit_cast(uint2, v);
-}
-__device__ __forceinline__ i32x2 read_b_tr8(const unsigned char* p) {
-    return __builtin_amdgcn_ds_read_tr8_b64_v2i32((i32x2 __attribute__((address_space(3)))*)(p));
-}
-
-// Lane-constant parts of the operand addresses inside a stage.
-template <class C> struct FragMap {
-    uint32_t a_kk[C::KK][C::APL];   // byte offsets of this lane's A piece(s) for k-step kk, block row 0
-    uint32_t b_ni[C::NI];           // byte offset of this lane's first B read for block column ni, k-step 0
-    __device__ __forceinline__ void init() {
-        const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
-        const int wm = wave / C::WN, wn = wave % C::WN;
-        const int row = wm * C::WTM + lane % C::MF;          // + mi * MF keeps row % 16
-#pragma unroll
-        for (int kk = 0; kk < C::KK; kk++)
-#pragma unroll
-            for (int i = 0; i < C::APL; i++)
-                a_kk[kk][i] = (row * C::CPA + ((kk * (C::KM / C::PE) + (lane / C::MF) * C::APL + i) ^ swz_a<C::CPA>(row))) * 16;
-        // rows of one transposing read: 4 (16-bit) or 8 (8-bit); later reads and k-steps add multiples of that
-        const int krow = C::KPL * (lane / C::MF) + (C::FP8 ? (lane % 16) / 2 : (lane % 16) / 4);
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ni++) {
-            const int col = wn * C::WTN + ni * C::MF + 16 * ((lane % C::MF) / 16) + (C::FP8 ? 8 * (lane % 2) : 4 * (lane % 4));
-            b_ni[ni] = (krow * C::CPB + ((col / C::PE) ^ swz_b<C::FP8>(krow))) * 16 + (col % C::PE) * C::ES;
-        }
-    }
-};
-
-template <class C, bool FP8 = C::FP8> struct Frags;
-template <class C> struct Frags<C, false> {
-    uint4 a[C::MI], b[C::NI];
-    __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++)
-            a[mi] = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][0] + mi * C::MF * C::CPA * 16);
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ni++) {
-            const unsigned char* p = b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16;
-            const uint2 lo = read_b_tr16(p), hi = read_b_tr16(p + 4 * C::CPB * 16);
-            b[ni] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        }
-    }
-};
-template <class C> struct Frags<C, true> {
-    i32x8 a[C::MI], b[C::NI];
-    __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++) {
-            const uint4 lo = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][0] + mi * C::MF * C::CPA * 16);
-            const uint4 hi = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][1] + mi * C::MF * C::CPA * 16);
-            a[mi] = i32x8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-        }
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ni++) {
-            const unsigned char* p = b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16;
-            const i32x2 q0 = read_b_tr8(p), q1 = read_b_tr8(p + 8 * C::CPB * 16);
-            const i32x2 q2 = read_b_tr8(p + 16 * C::CPB * 16), q3 = read_b_tr8(p + 24 * C::CPB * 16);
-            b[ni] = i32x8{q0[0], q0[1], q1[0], q1[1], q2[0], q2[1], q3[0], q3[1]};
-        }
-    }
-};
-
-__device__ __forceinline__ u16 to_bf16_bits(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u16)((u >> 16) | 0x40);   // quiet NaN
-    return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);                   // round to nearest even
-}
-
-template <class C, int LATER> __device__ __forceinline__ void wait_stage(int later) {
-    // wait until the loads of the wanted stage have landed, given how many stages follow it
-    if (LATER == 0 || later >= LATER) wait_vmcnt<C::in_flight(LATER)>();
-    else wait_stage<C, (LATER > 0 ? LATER - 1 : 0)>(later);
-}
-
-// The matrix-core work of one k-step.
-template <class C>
-__device__ __forceinline__ void mma_step(const Frags<C>& f, typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
-#pragma unroll
-    for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ni++)
-            acc[mi][ni] = Mfma<C::DT, C::MF>::run(f.a[mi], f.b[ni], acc[mi][ni]);
-}
-
-// All k-steps of one stage, for the register-staged path: the operands of step kk+1 are read from
-// LDS while the matrix cores work on step kk.
-template <class C>
-__device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm,
-                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
-    Frags<C> f[2];
-    f[0].load(a_stage, b_stage, fm, 0);
-#pragma unroll
-    for (int kk = 0; kk < C::KK; kk++) {
-        if (kk + 1 < C::KK) f[(kk + 1) & 1].load(a_stage, b_stage, fm, kk + 1);
-        mma_step<C>(f[kk & 1], acc);
-    }
-}
-
-// MAC loop of one segment (Algorithm 1, line 13): k-iterations [k_begin, k_end) of one tile.
-//
-// Software pipeline of the LDS-DMA path.  Stage s (one k-iteration) lives in A ring slot s % NSA and
-// B ring slot s % NSB.  The barrier that hands stage i+1 to the waves sits one k-step *before* the
-// end of stage i: by then every wave has read the operands of stage i's last k-step into registers,
-// so (1) stage i's slots can be refilled at once (with stages i+NSB / i+NSA), (2) the operands of
-// stage i+1's first k-step are read while the matrix cores still work on stage i's last one, and
-// (3) the time a wave spends at the barrier is covered by matrix-core work already queued.
-template <class C, bool ALIGNED>
-__device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int k_begin, int k_end,
-                                         unsigned char* smem, const FragMap<C>& fm,
-                                         typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
-    const int nk = k_end - k_begin;
-    if (C::DIRECT && ALIGNED) {
-        static_assert(!C::DIRECT || C::KK % 2 == 0, "operand double buffering assumes an even number of k-steps");
-        const uint32_t lds0 = (uint32_t)(size_t)(lds_byte*)smem;
-        const int full_k = g.K / C::BK;             // iterations below this index are entirely inside K
-        DmaMap<C> dm;
-        dm.init(g, m0, n0);
-        // request batch j (issued after the barrier of stage j): B tile of stage j+NSB, then A tile of
-        // stage j+NSA, into the slots of stage j; step / steps select a slice of the batch
-        auto issue_batch = [&](int j, int slot_a, int slot_b, int step, int steps) {
-            const int ib = j + C::NSB, ia = j + C::NSA;
-            const int q0 = step * C::LPS / steps, q1 = (step + 1) * C::LPS / steps;
-            const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
-            const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
-            if (ib >= 0 && ib < nk && b1 > b0) {
-                const uint32_t lds = lds0 + C::B_RING + slot_b * C::B_BYTES;
-                if (k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
-                else dm.template issue_b<true>(g, k_begin + ib, lds, b0, b1);
-            }
-            if (ia >= 0 && ia < nk && a1 > a0) {
-                const uint32_t lds = lds0 + slot_a * C::A_BYTES;
-                if (k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds, a0, a1);
-                else dm.template issue_a<true>(g, k_begin + ia, lds, a0, a1);
-            }
-        };
-        // the batches that stages before the first would have requested, all but the last
-#pragma unroll
-        for (int j = -C::NSA; j <= -2; j++)
-            issue_batch(j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
-        Frags<C> f[2];
-        int ca = C::NSA - 1, cb = C::NSB - 1;        // ring slots of stage i (i = -1: the slots batch -1 fills)
-        // one trip = [barrier that hands over stage i+1] [requests of batch i, sliced over the k-steps]
-        //            [last k-step of stage i] [k-steps 0 .. KK-2 of stage i+1]; FIRST: i = -1, no stage i yet
-        auto trip = [&](int i, auto first) {
-            constexpr bool FIRST = decltype(first)::value;
-            const bool has_next = i + 1 < nk;
-            const int na = ca + 1 == C::NSA ? 0 : ca + 1, nb = cb + 1 == C::NSB ? 0 : cb + 1;   // slots of stage i+1
-            const unsigned char* a_next = smem + na * C::A_BYTES;
-            const unsigned char* b_next = smem + C::B_RING + nb * C::B_BYTES;
-            if (has_next) {
-                wait_stage<C, C::NSA - 1>(nk - 2 - i);   // stage i+1 has landed (this wave's share)
-                __syncthreads();                         // ... and everybody's; stage i's slots are free
-                f[0].load(a_next, b_next, fm, 0);
-            }
-            issue_batch(i, ca, cb, 0, C::KK);
-            if (!FIRST) mma_step<C>(f[1], acc);          // last k-step of stage i
-            if (has_next) {
-#pragma unroll
-                for (int kk = 0; kk < C::KK - 1; kk++) {
-                    f[(kk + 1) & 1].load(a_next, b_next, fm, kk + 1);
-                    issue_batch(i, ca, cb, kk + 1, C::KK);
-                    mma_step<C>(f[kk & 1], acc);
-                }
-            }
-            ca = na;
-            cb = nb;
-        };
-        trip(-1, std::true_type());
-        for (int i = 0; i < nk; i++) trip(i, std::false_type());
-        __syncthreads();                             // all reads done before the next segment refills
-    } else {
-        for (int k = k_begin; k < k_end; k++) {
-            const int slot = (k - k_begin) & 1;
-            unsigned char* a_stage = smem + slot * C::A_BYTES;
-            unsigned char* b_stage = smem + C::B_RING + slot * C::B_BYTES;
-            fill_stage_staged<C, ALIGNED>(g, m0, n0, k, a_stage, b_stage);
-            __syncthreads();
-            mac_stage<C>(a_stage, b_stage, fm, acc);
-        }
-        __syncthreads();
-    }
-}
-
-// Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): per accumulator block, add the
-// parked partials of the contributors in ascending workgroup order (= ascending k), convert and
-// store.  OUT selects the output type, EDGE adds the bounds checks.  Working one block at a time
-// keeps the register need flat.
-template <class C, int OUT, bool EDGE>
-__device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
-                                                 const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
-    typedef typename Mfma<C::DT, C::MF>::Acc Acc;
-#pragma unroll
-    for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ni++) {
-            Acc blk = acc[mi][ni];
-            const float* src = part0 + ((mi * C::NI + ni) * C::ACC) * C::THREADS;
-            for (int c = 0; c < n_contrib; c++) {
-                float v[C::ACC];
-#pragma unroll
-                for (int r = 0; r < C::ACC; r++)
-                    v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
-                src += C::BM * C::BN;
-            }
-            const int col = col0 + ni * C::MF;
-#pragma unroll
-            for (int r = 0; r < C::ACC; r++) {
-                const int row = row0 + mi * C::MF + (r / 4) * (4 * C::KG) + r % 4;
-                if (!EDGE || (row < g.M && col < g.N)) {
-                    const size_t o = (size_t)((uint32_t)row * (uint32_t)g.N + (uint32_t)col);
-                    const float v = blk[r];
-                    if (OUT == SK_F32) static_cast<float*>(g.D)[o] = v;
-                    else if (OUT == SK_BF16) static_cast<u16*>(g.D)[o] = to_bf16_bits(v);
-                    else static_cast<_Float16*>(g.D)[o] = (_Float16)v;
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-}
-
-template <class C, bool ALIGNED>
-__global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
-    extern __shared__ __align__(1024) unsigned char smem[];
-    typedef typename Mfma<C::DT, C::MF>::Acc Acc;
-    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
-    const int wm = wave / C::WN, wn = wave % C::WN;
-    const int x = logical_wg(blockIdx.x, g.grid);
-    FragMap<C> fm;
-    fm.init();
-
-    // Algorithm 1, lines 5-6 (clamped): this workgroup's share of the Stream-K iterations
-    int it = x * g.ipw, it_end = it + g.ipw;
-    if (it > g.sk_iters) it = g.sk_iters;
-    if (it_end > g.sk_iters) it_end = g.sk_iters;
-    int dp_tile = g.sk_tiles + x;   // data-parallel tiles come after the Stream-K work
-
-    while (true) {
-        int tile, k_begin, k_end;
-        if (it < it_end) {                       // Algorithm 1, lines 8-12
-            tile = (int)((uint32_t)it / (uint32_t)g.ipt);
-            const int tile_first = tile * g.ipt;
-            k_begin = it - tile_first;
-            const int stop = it_end < tile_first + g.ipt ? it_end : tile_first + g.ipt;
-            k_end = stop - tile_first;
-            it = tile_first + g.ipt;
-        } else if (dp_tile < g.tiles) {
-            tile = dp_tile; k_begin = 0; k_end = g.ipt;
-            dp_tile += g.grid;
-        } else {
-            break;
-        }
-        int tm, tn;
-        if (g.tile_order == SK_ORDER_ROW_MAJOR) {
-            tm = (int)((uint32_t)tile / (uint32_t)g.tiles_n);
-            tn = tile - tm * g.tiles_n;
-        } else {                                 // bands of 8 tile rows, walked column by column
-            const uint32_t per_band = (uint32_t)(SK_GROUP_ROWS * g.tiles_n);
-            const uint32_t band = (uint32_t)tile / per_band, within = (uint32_t)tile - band * per_band;
-            const int left = g.tiles_m - (int)band * SK_GROUP_ROWS;
-            const uint32_t rows = (uint32_t)(left < SK_GROUP_ROWS ? left : SK_GROUP_ROWS);
-            tn = (int)(within / rows);
-            tm = (int)band * SK_GROUP_ROWS + (int)(within - (uint32_t)tn * rows);
-        }
-        const int m0 = tm * C::BM, n0 = tn * C::BN;
-
-        Acc acc[C::MI][C::NI];
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
-        mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, acc);
-
-        // ---- fix-up
-        // (the empty asm statements keep the per-block addresses from being computed once, ahead
-        // of the persistent loop, where they would occupy registers for the whole kernel)
-        if (k_begin > 0) {
-            // contributor: park the accumulators (register order, coalesced), then signal
-            // Partial tiles are stored and loaded with device-scope atomic accesses (one dword
-            // per lane, lanes contiguous): these are coherent across the XCDs' L2 caches by
-            // themselves, so no L2 write-back / invalidate is needed around the exchange.
-            float* slot = g.partials + (size_t)x * (C::BM * C::BN) + tid;
-            asm volatile("" : "+v"(slot));
-#pragma unroll
-            for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-                for (int ni = 0; ni < C::NI; ni++) {
-#pragma unroll
-                    for (int r = 0; r < C::ACC; r++)
-                        __hip_atomic_store(slot + ((mi * C::NI + ni) * C::ACC + r) * C::THREADS, acc[mi][ni][r],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            wait_vmcnt<0>();                      // every lane's part of the partial tile has reached memory
-            __syncthreads();
-            if (tid == 0)
-                __hip_atomic_store(g.flags + (size_t)x * (SK_FLAG_STRIDE / 4), g.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            continue;
-        }
-        int n_contrib = 0;
-        if (k_end < g.ipt) {
-            // owner: contributors are the following workgroups up to the one holding the tile's
-            // last iteration.  Wait for all of them; the epilogue adds their partials in a fixed
-            // order, so the result does not depend on timing.
-            const int last = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
-            if (tid == 0) {
-                uint32_t polls = 0;
-                for (int c = x + 1; c <= last; c++) {
-                    while (__hip_atomic_load(g.flags + (size_t)c * (SK_FLAG_STRIDE / 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.epoch) {
-                        if (polls++ >= g.spin_limit) {   // bounded wait: record and go on
-                            __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(2);
-                    }
-                }
-            }
-            __syncthreads();
-            n_contrib = last - x;
-        }
-
-        // ---- epilogue: fp32 accumulators -> D
-        int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
-        asm volatile("" : "+v"(row0), "+v"(col0));
-        const float* part0 = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
-        asm volatile("" : "+v"(part0));
-        const bool edge = m0 + C::BM > g.M || n0 + C::BN > g.N;
-        if (g.out_dtype == SK_BF16) {
-            if (edge) reduce_and_store<C, SK_BF16, true>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_BF16, false>(g, row0, col0, part0, n_contrib, acc);
-        } else if (g.out_dtype == SK_F16) {
-            if (edge) reduce_and_store<C, SK_F16, true>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F16, false>(g, row0, col0, part0, n_contrib, acc);
-        } else {
-            if (edge) reduce_and_store<C, SK_F32, true>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F32, false>(g, row0, col0, part0, n_contrib, acc);
-        }
-    }
-}
-
-// ---- host side ---------------------------------------------------------------------------------
-typedef void (*kernel_fn)(GemmArgs);
-struct KernelEntry {
-    int dtype, bm, bn, bk, variant;
-    kernel_fn aligned, generic;
-    int threads, lds_bytes, piece_elems;
-    std::atomic<int> max_resident{-1};   // co-resident workgroups on the device, -1 = not yet asked
-    KernelEntry(int d, int m, int n, int k, int v, kernel_fn a, kernel_fn g, int t, int l, int pe)
-        : dtype(d), bm(m), bn(n), bk(k), variant(v), aligned(a), generic(g), threads(t), lds_bytes(l), piece_elems(pe) {}
-};
-
-template <class C> KernelEntry* make_entry(int variant = 0) {
-    return new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, streamk_gemm_kernel<C, true>, streamk_gemm_kernel<C, false>,
-                           C::THREADS, C::LDS_BYTES, C::PE);
-}
-
-// Tile shapes with a kernel: <dtype, BM, BN, BK, waves along M, waves along N, matrix-core block,
-// A ring depth[, B ring depth]>.
-// Variant 0 of a shape is the one sk_gemm uses; other variants are alternative wave layouts of the
-// same shape, selectable with the environment variable SK_KERNEL_VARIANT for tuning runs.
-template <int DT> void add_dtype(KernelEntry** t, int* n) {
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 2, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2>>(1);
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 2, 2>>(2);
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 4, 32, 4>>(1);
-    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>>();
-}
 
 KernelEntry** kernel_table(int* count) {
     static KernelEntry* table[64];
     static int n = 0;
     static std::once_flag once;
     std::call_once(once, [] {
-        add_dtype<SK_BF16>(table, &n);
-        add_dtype<SK_F16>(table, &n);
-        // 8-bit inputs: same byte footprint per stage as the 16-bit tiles with twice the k
-        table[n++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 4, 32, 3, 2>>();
-        table[n++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 2, 32, 3, 2>>(1);
-        table[n++] = make_entry<Cfg<SK_FP8_E4M3, 128, 256, 128, 2, 4, 32, 3, 3>>();
+        register_bf16(table, &n);
+        register_f16(table, &n);
+        register_fp8(table, &n);
     });
     *count = n;
     return table;

@@ -6,7 +6,7 @@ were never profiled, its shape key, see bloom_shape_key) is inserted into the fi
 winner.  A query returns the candidate policies; the profiler then times only those, or - when no
 timing is wanted - the candidate that won most often in the build set is taken.
 
-    python -m paper_2408_11417_amd.selector --sweep gpurun_out/sweep_bf16.json --split 400
+    python -m paper_2408_11417_amd.selector --sweep sweep_bf16.json --split 400
 
 prints, for tolerances 0 / 5 % / 20 %: false negatives on the build split, pruning rate, and on
 the held-out split the ratio selected / best and the share of shapes at >= 90 % of the best.

@@ -5,7 +5,7 @@ Stream-K++ policies are launched with warm-up + timed repetitions (50 + 50 for s
 for long ones) and the mean kernel time is kept.  The output feeds `selector.py`, which builds the
 Bloom filters (Sec. 4.2) from the winners and evaluates them on held-out shapes.
 
-    python -m paper_2408_11417_amd.sweep --shapes 500 --seed 4 --out gpurun_out/sweep.json
+    python -m paper_2408_11417_amd.sweep --shapes 500 --seed 4 --out sweep_bf16.json
 
 Needs a GPU.  Inputs are seeded synthetic bf16 matrices, uniform in [-1, 1], carved out of two
 device pools that are filled once.
@@ -113,7 +113,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--shapes", type=int, default=500)
     ap.add_argument("--seed", type=int, default=4)
-    ap.add_argument("--out", default="gpurun_out/sweep.json")
+    ap.add_argument("--out", default="sweep_bf16.json")
     ap.add_argument("--first", type=int, default=0, help="only the first N shapes (smoke runs)")
     args = ap.parse_args()
     from paper_2408_11417_amd import inputs
