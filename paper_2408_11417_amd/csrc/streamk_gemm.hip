@@ -13,8 +13,10 @@ KernelEntry** kernel_table(int* count) {
     static std::once_flag once;
     std::call_once(once, [] {
         register_bf16(table, &n);
+#ifndef SK_ONLY_BF16   // (tuning builds that compile one input type only)
         register_f16(table, &n);
         register_fp8(table, &n);
+#endif
     });
     *count = n;
     return table;
