@@ -6,8 +6,9 @@ plan.  Before the timed region a tuning pass times all seven policies (50 warm-u
 launches each, the paper's protocol, Sec. 5.1) and builds the filters from the policies within 20 %
 of the best (Sec. 4.2).  Inputs are seeded synthetic matrices already resident in HBM.
 
-Prints ONE JSON line: TFLOP/s of the Bloom-selected policy, the MFMA roofline of the GEMM kernel
-(HIP events around each launch, on the launch stream) and the CPU oracle timed on the host cores.
+Prints ONE JSON line: TFLOP/s of the Bloom-selected policy, the roofline of the GEMM kernel (MFMA
+peak; HBM bandwidth for the skinny workloads; kernel time from HIP events on the launch stream around
+back-to-back launches) and the CPU oracle timed on the host cores.
 """
 import argparse
 import json
@@ -18,7 +19,7 @@ import numpy as np
 
 # HBM bytes per launch of the data-parallel policy on the default workload, from rocprofv3
 # FETCH_SIZE / WRITE_SIZE scaled by a plain-copy calibration (profiles/streamk_gemm_kernel_cfg2_bf16_3840x4224x4096.txt)
-MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.4e6 + 32.4e6}
+MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.3e6 + 32.6e6}
 PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "e4m3": 5033.2}    # dense MFMA peak of MI355X
 
 
@@ -65,10 +66,16 @@ def main():
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
-        for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        e0.record()
+        for _ in range(4):
             dst.copy_(src)
+        e1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
+        ms = e0.elapsed_time(e1) / 4
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5,
+                          "copy_ms": round(ms, 4), "copy_read_plus_write_GBps": round(2 * src.numel() * 4 / ms / 1e6, 1)}))
         return 0
     stream = torch.cuda.current_stream().cuda_stream
     c = workload(args.workload)
@@ -78,6 +85,13 @@ def main():
     dA = torch.from_numpy(c["A"].view(np.int16 if dt != 2 else np.uint8)).cuda()
     dB = torch.from_numpy(c["B"].view(np.int16 if dt != 2 else np.uint8)).cuda()
     D = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    # The skinny workloads are bound by reading B once from HBM; B (134 MB) would stay in the
+    # 256 MB memory-side cache between launches, so they rotate over four copies of A, B and D.
+    hbm_bound = args.workload.startswith("cfg3")
+    sets = [(dA, dB, D)]
+    if hbm_bound:
+        sets += [(dA.clone(), dB.clone(), torch.empty_like(D)) for _ in range(3)]
+    launches = [0]
 
     plans, keep = {}, []
     for p in range(sk.SK_NUM_POLICIES):
@@ -89,16 +103,18 @@ def main():
         plans[p] = plan
     info = sk.sk_plan_info(plans[0])
 
-    def launch(p):
-        sk.sk_gemm(dA.data_ptr(), dB.data_ptr(), D.data_ptr(), plans[p], stream)
+    def launch(p, plan_set=None):
+        a, b, d = sets[launches[0] % len(sets)]
+        launches[0] += 1
+        sk.sk_gemm(a.data_ptr(), b.data_ptr(), d.data_ptr(), (plan_set or plans)[p], stream)
 
-    def time_policy(p, warm, timed):
+    def time_policy(p, warm, timed, plan_set=None):
         for _ in range(warm):
-            launch(p)
+            launch(p, plan_set)
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(timed)]
         for e0, e1 in evs:
             e0.record()
-            launch(p)
+            launch(p, plan_set)
             e1.record()
         torch.cuda.synchronize()
         return float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))   # ms per launch
@@ -130,11 +146,47 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     assert sk.sk_plan_check(plans[sel], stream) == sk.SK_OK
-    kernel_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    # kernel time of the selected policy: the same number of launches back to back between one pair
+    # of events on the launch stream (per-launch event pairs would add the launch gap, which matters
+    # for the 30 us skinny kernels)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        launch(sel)
+    e1.record()
+    torch.cuda.synchronize()
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    step_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
     ms_per_step = wall * 1e3 / args.steps
     value = flops / (ms_per_step * 1e-3) / 1e12
-    achieved = flops / (kernel_ms * 1e-3) / 1e12
-    peak = PEAK_TFLOPS[dtype_name]
+    alg_bytes = (M * K + K * N) * (1 if dt == 2 else 2) + M * N * 2
+    if hbm_bound:
+        roofline = {"bound": "hbm", "achieved": round(alg_bytes / (kernel_ms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s"}
+    else:
+        roofline = {"bound": "mfma", "achieved": round(flops / (kernel_ms * 1e-3) / 1e12, 2), "peak": PEAK_TFLOPS[dtype_name],
+                    "unit": "TFLOP/s"}
+    roofline["frac"] = round(roofline["achieved"] / roofline["peak"], 4)
+
+    # the same problem under the tile the library would pick by itself (best policy), when the
+    # workload prescribes another one
+    own_tile = None
+    if c["blk"] is not None and args.policy < 0:
+        own, keep2 = {}, []
+        for p in range(sk.SK_NUM_POLICIES):
+            plan = sk.sk_plan(M, N, K, p, None, c["grid"], dt, c["out_dtype"])
+            nbytes = sk.sk_workspace_bytes(plan)
+            ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+            sk.sk_plan_set_workspace(plan, (ws.data_ptr() + 255) // 256 * 256, nbytes)
+            keep2.append(ws)
+            own[p] = plan
+        oi = sk.sk_plan_info(own[0])
+        if (oi["blk_m"], oi["blk_n"], oi["blk_k"]) != (info["blk_m"], info["blk_n"], info["blk_k"]):
+            t_own = {p: time_policy(p, 20, 20, own) for p in own}
+            pb = min(t_own, key=t_own.get)
+            own_tile = {"tile": [oi["blk_m"], oi["blk_n"], oi["blk_k"]], "best_policy": sk.POLICY_NAMES[pb],
+                        "tflops": round(flops / (t_own[pb] * 1e-3) / 1e12, 2)}
+        for plan in own.values():
+            sk.sk_plan_destroy(plan)
 
     out = {
         "metric": "gemm_tflops_bloom_selected_policy", "value": round(value, 2), "unit": "TFLOP/s",
@@ -143,16 +195,16 @@ def main():
         "data": "synthetic",
         "config": {"workload": c["label"], "M": M, "N": N, "K": K,
                    "tile": [info["blk_m"], info["blk_n"], info["blk_k"]], "grid": info["grid"]},
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                     "frac": round(achieved / peak, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, sk.POLICY_NAMES[sel])),
-                     "algorithmic_bytes": (M * K + K * N) * (1 if dt == 2 else 2) + M * N * 2,
-                     "kernel": "streamk_gemm_kernel", "kernel_ms": round(kernel_ms, 5)},
+        "roofline": dict(roofline, traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, sk.POLICY_NAMES[sel])),
+                         algorithmic_bytes=alg_bytes, kernel="streamk_gemm_kernel", kernel_ms=round(kernel_ms, 5),
+                         step_event_ms=round(step_ms, 5)),
         "selected_policy": sk.POLICY_NAMES[sel],
         "selected_over_best": round(best / t_pol[sel], 4),
         "policies_tflops": {sk.POLICY_NAMES[p]: round(flops / (t * 1e-3) / 1e12, 2) for p, t in t_pol.items()},
         "bloom_candidates": [sk.POLICY_NAMES[p] for p in t_pol if (mask >> p) & 1],
     }
+    if own_tile:
+        out["library_default_tile"] = own_tile
 
     if not args.no_cpu_baseline:
         from oracle import gemm as G

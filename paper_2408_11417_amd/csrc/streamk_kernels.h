@@ -120,6 +120,12 @@ struct Cfg {
     static constexpr int LPS = A_LD + B_LD;              // LDS-DMA loads per stage per wave
     // register-staged fill (unaligned problems, tiles too small for the DMA split)
     static constexpr int CA = (A_PIECES + THREADS - 1) / THREADS, CB = (B_PIECES + THREADS - 1) / THREADS;
+    // Registers of one set of matrix-core operands and of the accumulators.  With 8 waves a lane has
+    // 256 registers for everything; with 4 waves 256 plus 256 that can hold the accumulators.
+    // PIN_ORDER: there is room to hold two operand sets, so the MAC loop pins "read the next
+    // k-step's operands, then multiply the current ones".
+    static constexpr int FRAG_REGS = (MI + NI) * (FP8 ? 8 : 4), ACC_REGS = MI * NI * ACC;
+    static constexpr bool PIN_ORDER = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 64 <= 256 : 2 * FRAG_REGS + 64 <= 160;
     static_assert(WTM % MF == 0 && WTN % MF == 0 && BK % KM == 0, "tile does not divide");
     static_assert(CPA == 4 || CPA == 8 || CPA == 16, "A swizzle assumes 64/128/256-byte rows");
     static_assert(CPB >= 16, "B swizzle assumes rows of at least 256 bytes");
@@ -446,11 +452,19 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
             issue_batch(j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
         Frags<C> f[2];
         int ca = C::NSA - 1, cb = C::NSB - 1;        // ring slots of stage i (i = -1: the slots batch -1 fills)
-        // one trip = [barrier that hands over stage i+1] [requests of batch i, sliced over the k-steps]
-        //            [last k-step of stage i] [k-steps 0 .. KK-2 of stage i+1]; FIRST: i = -1, no stage i yet
-        auto trip = [&](int i, auto first) {
+        // one trip = [barrier that hands over stage i+1] [operands of stage i+1's first k-step]
+        //            [requests of batch i, sliced over the k-steps] [last k-step of stage i]
+        //            [k-steps 0 .. KK-2 of stage i+1, each preceded by the operand reads of the next one].
+        // FIRST: i = -1, no stage i yet.  NEXT: whether a stage i+1 exists.  Where registers allow two
+        // operand sets (PIN_ORDER), NEXT is a compile-time fact - the steady-state loop body then has
+        // no joins between the LDS reads and the matrix-core work (the compiler's wait-count
+        // bookkeeping merges conservatively at joins) - and scheduling barriers keep the reads of
+        // k-step kk+1 ahead of the matrix-core work of k-step kk.  Otherwise the compiler is left
+        // to order reads and matrix-core work so that one operand set suffices.
+        auto trip = [&](int i, auto first, auto next) {
             constexpr bool FIRST = decltype(first)::value;
-            const bool has_next = i + 1 < nk;
+            constexpr int NEXT = decltype(next)::value;          // 1 / 0: known, -1: decided at run time
+            const bool has_next = NEXT < 0 ? i + 1 < nk : NEXT == 1;
             const int na = ca + 1 == C::NSA ? 0 : ca + 1, nb = cb + 1 == C::NSB ? 0 : cb + 1;   // slots of stage i+1
             const unsigned char* a_next = smem + na * C::A_BYTES;
             const unsigned char* b_next = smem + C::B_RING + nb * C::B_BYTES;
@@ -460,20 +474,32 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
                 f[0].load(a_next, b_next, fm, 0);
             }
             issue_batch(i, ca, cb, 0, C::KK);
+            if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
             if (!FIRST) mma_step<C>(f[1], acc);          // last k-step of stage i
             if (has_next) {
 #pragma unroll
                 for (int kk = 0; kk < C::KK - 1; kk++) {
+                    if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
                     f[(kk + 1) & 1].load(a_next, b_next, fm, kk + 1);
                     issue_batch(i, ca, cb, kk + 1, C::KK);
+                    if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
                     mma_step<C>(f[kk & 1], acc);
                 }
             }
             ca = na;
             cb = nb;
         };
-        trip(-1, std::true_type());
-        for (int i = 0; i < nk; i++) trip(i, std::false_type());
+        typedef std::integral_constant<int, 1> Yes;
+        typedef std::integral_constant<int, 0> No;
+        typedef std::integral_constant<int, -1> AtRunTime;
+        if (C::PIN_ORDER) {
+            trip(-1, std::true_type(), Yes());
+            for (int i = 0; i < nk - 1; i++) trip(i, std::false_type(), Yes());
+            trip(nk - 1, std::false_type(), No());
+        } else {
+            trip(-1, std::true_type(), AtRunTime());
+            for (int i = 0; i < nk; i++) trip(i, std::false_type(), AtRunTime());
+        }
         __syncthreads();                             // all reads done before the next segment refills
     } else {
         for (int k = k_begin; k < k_end; k++) {
