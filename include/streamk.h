@@ -67,6 +67,16 @@ typedef enum {
     SK_ROLE_CONTRIB = 2  /* starts after K-iteration 0: stores an fp32 partial tile and signals */
 } sk_role;
 
+/* How the partial results of a split tile are combined.
+ * FLAGS (default): the workspace-and-flags exchange described at sk_role, the
+ * alternative Sec. 5.3 names; the owner adds the partials in ascending workgroup
+ * order, so D is bit-identical from run to run.
+ * ATOMIC: Algorithm 1, lines 14-18, as printed: every workgroup that holds only
+ * part of a tile's K-iterations adds its accumulators into a zero-initialised
+ * fp32 image of D with atomic adds, nobody waits for anybody.  The order of the
+ * additions depends on timing, so D may differ in the last bits between runs. */
+typedef enum { SK_FIXUP_FLAGS = 0, SK_FIXUP_ATOMIC = 1 } sk_fixup;
+
 /* How a tile index maps to a position in the tile grid.  The schedule (which
  * workgroup runs which tile index) does not depend on it.  GROUPED follows the
  * remark of Sec. 5.3 that work should be handed out with cache locality in
@@ -147,8 +157,16 @@ int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t cap, size_t*
  * INVALID_ARG if tile is outside [0, tiles). */
 int sk_plan_tile_coords(const sk_plan_t* plan, int32_t tile, int32_t* tile_m, int32_t* tile_n);
 
-/* Device bytes sk_gemm needs for this plan: one flag line per workgroup, a
- * status word, and one fp32 partial tile (blk_m * blk_n) per workgroup.
+/* Choose the fix-up of split tiles (sk_fixup; Algorithm 1, lines 14-18 for
+ * ATOMIC, Sec. 5.3 for FLAGS).  Call it before sk_workspace_bytes /
+ * sk_plan_set_workspace: the workspace need depends on it.
+ * Errors: INVALID_ARG (unknown mode, or a workspace is already attached). */
+int sk_plan_set_fixup(sk_plan_t* plan, int fixup);
+
+/* Device bytes sk_gemm needs for this plan.  FLAGS: one flag line per workgroup,
+ * a status word, and one fp32 partial tile (blk_m * blk_n) per workgroup.
+ * ATOMIC: the flag and status lines, plus an fp32 image of D (M * N * 4 bytes)
+ * unless the plan's output type is SK_F32 (then D itself is accumulated into).
  * Returns 0 for a NULL plan. */
 size_t sk_workspace_bytes(const sk_plan_t* plan);
 
@@ -168,8 +186,12 @@ int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls);
 /* D = A * B under the plan (Algorithm 1 with its MAC loop on the matrix cores;
  * Sec. 4.1 persistent grid; fix-up per Sec. 5.3).  A, B, D: device pointers in
  * the plan's dtypes and the row-major layout stated above.  stream: a
- * hipStream_t (NULL = the null stream).  Asynchronous: enqueues one kernel and
- * returns; never synchronises.  D is fully overwritten.
+ * hipStream_t (NULL = the null stream).  Asynchronous: enqueues its kernels and
+ * returns; never synchronises.  D is fully overwritten.  With SK_FIXUP_FLAGS that
+ * is one kernel.  With SK_FIXUP_ATOMIC and a plan that splits tiles it is a fill
+ * kernel that zeroes the fp32 image, the GEMM kernel, and - for 16-bit outputs -
+ * a conversion kernel from the fp32 image to D; plans without split tiles run
+ * the same single kernel under both modes.
  * Errors: INVALID_ARG, UNSUPPORTED (no kernel for tile + dtype, or the grid
  * cannot be co-resident while the plan has split tiles), WORKSPACE (plan has
  * split tiles but no workspace), HIP (launch failed). */

@@ -14,7 +14,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstreamk.so")
 SOURCES = ["streamk_plan.cpp", "streamk_bloom.cpp", "streamk_gemm.hip",
-           "streamk_gemm_bf16.hip", "streamk_gemm_f16.hip", "streamk_gemm_fp8.hip"]
+           "streamk_gemm_bf16.hip", "streamk_gemm_f16.hip", "streamk_gemm_fp8.hip",
+           "streamk_gemm_bf16_atomic.hip", "streamk_gemm_f16_atomic.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -38,7 +39,7 @@ def build_library(verbose=False, extra_flags=()):
     objs = [os.path.join(OBJ, s.rsplit(".", 1)[0] + ".o") for s in SOURCES]
     cmds = [[HIPCC] + FLAGS + list(extra_flags) + inc + ["-c", os.path.join(CSRC, s), "-o", o]
             for s, o in zip(SOURCES, objs)]
-    with ThreadPoolExecutor(max_workers=min(len(cmds), int(os.environ.get("MAX_JOBS", "6")))) as pool:
+    with ThreadPoolExecutor(max_workers=min(len(cmds), int(os.environ.get("MAX_JOBS", "8")))) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
     return LIB

@@ -16,20 +16,23 @@ KernelEntry** kernel_table(int* count) {
 #ifndef SK_ONLY_BF16   // (tuning builds that compile one input type only)
         register_f16(table, &n);
         register_fp8(table, &n);
+        register_bf16_atomic(table, &n);
+        register_f16_atomic(table, &n);
+        register_fp8_atomic(table, &n);
 #endif
     });
     *count = n;
     return table;
 }
 
-KernelEntry* find_kernel(int dtype, int bm, int bn, int bk) {
+KernelEntry* find_kernel(int dtype, int bm, int bn, int bk, int fixup = SK_FIXUP_FLAGS) {
     int n;
     KernelEntry** t = kernel_table(&n);
     const char* env = getenv("SK_KERNEL_VARIANT");
     const int want = env ? atoi(env) : 0;
     KernelEntry* fallback = nullptr;
     for (int i = 0; i < n; i++)
-        if (t[i]->dtype == dtype && t[i]->bm == bm && t[i]->bn == bn && t[i]->bk == bk) {
+        if (t[i]->dtype == dtype && t[i]->bm == bm && t[i]->bn == bn && t[i]->bk == bk && t[i]->fixup == fixup) {
             if (t[i]->variant == want) return t[i];
             if (t[i]->variant == 0) fallback = t[i];
         }
@@ -37,6 +40,20 @@ KernelEntry* find_kernel(int dtype, int bm, int bn, int bk) {
 }
 
 std::atomic<uint32_t> g_epoch{0};
+
+// Helpers of the atomic fix-up: clear the fp32 image, and turn it into a 16-bit D afterwards.
+__global__ void zero_image_kernel(float4* p, size_t n4, float* tail, int n_tail) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && (int)threadIdx.x < n_tail) tail[threadIdx.x] = 0.f;
+}
+template <int OUT> __global__ void convert_image_kernel(const float* src, void* dst, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        if (OUT == SK_BF16) static_cast<u16*>(dst)[i] = to_bf16_bits(src[i]);
+        else static_cast<_Float16*>(dst)[i] = (_Float16)src[i];
+    }
+}
 
 thread_local hipError_t g_last_hip = hipSuccess;   // last failing HIP call of this thread
 inline bool hip_ok(hipError_t e) {
@@ -84,9 +101,11 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     // the kernels use 32-bit byte offsets into A and B, 32-bit element offsets into D and 32-bit iteration counts
     if (h.M * h.K >= (1ll << 31) || h.K * h.N >= (1ll << 31) || h.M * h.N >= (1ll << 32) || h.total_iters >= (1ll << 30))
         return SK_ERR_UNSUPPORTED;
-    KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k);
+    // plans without split tiles run the plain kernel under either fix-up mode
+    const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
+    KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS);
     if (!e) return SK_ERR_UNSUPPORTED;
-    if (plan->needs_fixup && !plan->workspace) return SK_ERR_WORKSPACE;
+    if (plan->needs_fixup && !plan->workspace && !(atomic && h.out_dtype == SK_F32)) return SK_ERR_WORKSPACE;
     const bool aligned = (h.K % e->piece_elems == 0) && (h.N % e->piece_elems == 0);   // whole 16-byte pieces per row
     kernel_fn fn = aligned ? e->aligned : e->generic;
 
@@ -103,7 +122,8 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
         e->max_resident.store(per_cu * cus);
     }
     // an owner spins on flags of other workgroups: all of them must be on the machine at once
-    if (plan->needs_fixup && h.grid > e->max_resident.load()) return SK_ERR_UNSUPPORTED;
+    if (plan->needs_fixup && !atomic && h.grid > e->max_resident.load()) return SK_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
 
     GemmArgs g{};
     g.A = A; g.B = B; g.D = D;
@@ -119,6 +139,21 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.epoch = ep;
     g.spin_limit = plan->spin_limit;
     g.out_dtype = h.out_dtype;
-    hipLaunchKernelGGL(fn, dim3(h.grid), dim3(e->threads), e->lds_bytes, static_cast<hipStream_t>(stream), g);
+    if (atomic) {
+        // Algorithm 1, lines 14-18 need C to start at zero: clear the image in-stream, accumulate, convert
+        const size_t n = (size_t)h.M * (size_t)h.N;
+        g.image = h.out_dtype == SK_F32 ? static_cast<float*>(D) : g.partials;
+        const int blocks = (int)((n / 4 + 255) / 256 < 2048 ? (n / 4 + 255) / 256 : 2048);
+        hipLaunchKernelGGL(zero_image_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, st,
+                           reinterpret_cast<float4*>(g.image), n / 4, g.image + (n / 4) * 4, (int)(n % 4));
+        hipLaunchKernelGGL(fn, dim3(h.grid), dim3(e->threads), e->lds_bytes, st, g);
+        if (h.out_dtype != SK_F32) {
+            const int cb = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+            if (h.out_dtype == SK_BF16) hipLaunchKernelGGL(convert_image_kernel<SK_BF16>, dim3(cb), dim3(256), 0, st, g.image, D, n);
+            else hipLaunchKernelGGL(convert_image_kernel<SK_F16>, dim3(cb), dim3(256), 0, st, g.image, D, n);
+        }
+        return hip_ok(hipGetLastError()) ? SK_OK : SK_ERR_HIP;
+    }
+    hipLaunchKernelGGL(fn, dim3(h.grid), dim3(e->threads), e->lds_bytes, st, g);
     return hip_ok(hipGetLastError()) ? SK_OK : SK_ERR_HIP;
 }

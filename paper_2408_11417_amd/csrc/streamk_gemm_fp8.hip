@@ -7,4 +7,8 @@ void register_fp8(KernelEntry** t, int* n) {
     t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 2, 32, 3, 2>>(1);
     t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 128, 256, 128, 2, 4, 32, 3, 3>>();
 }
+void register_fp8_atomic(KernelEntry** t, int* n) {
+    t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 4, 32, 3, 2>, true>();
+    t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 128, 256, 128, 2, 4, 32, 3, 3>, true>();
+}
 }  // namespace streamk_detail

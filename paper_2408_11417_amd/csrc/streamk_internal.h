@@ -10,6 +10,7 @@ struct sk_plan_t {
     size_t workspace_bytes = 0;
     uint32_t spin_limit = 1u << 24;
     int needs_fixup = 0;            // 1 if any tile is split over several workgroups
+    int fixup = SK_FIXUP_FLAGS;     // how split tiles are combined
 };
 
 // Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]
@@ -20,3 +21,7 @@ inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_F
 
 // Does the GEMM launcher hold a kernel for this configuration?
 bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k);
+// Bytes of the fp32 image of D that the atomic fix-up accumulates into (0 if D itself serves).
+inline size_t sk_ws_image_bytes(const sk_plan_t* p) {
+    return p->fixup == SK_FIXUP_ATOMIC && p->h.out_dtype != SK_F32 ? (size_t)p->h.M * (size_t)p->h.N * sizeof(float) : 0;
+}

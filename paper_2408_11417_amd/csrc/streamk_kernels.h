@@ -37,6 +37,7 @@ struct GemmArgs {
     const void* B;
     void* D;
     float* partials;       // grid slots of BM*BN floats
+    float* image;          // atomic fix-up: fp32 image of D that partial tiles are added into (D itself for fp32 output)
     uint32_t* flags;       // one per workgroup, SK_FLAG_STRIDE bytes apart
     uint32_t* status;      // set non-zero when an owner gives up waiting
     int M, N, K;
@@ -516,26 +517,55 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
 
 // Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): per accumulator block, add the
 // parked partials of the contributors in ascending workgroup order (= ascending k), convert and
-// store.  OUT selects the output type, EDGE adds the bounds checks.  Working one block at a time
-// keeps the register need flat.
+// store.  OUT selects the output type, EDGE adds the bounds checks.  The big tiles work one block at
+// a time, which keeps their register need flat.
 template <class C, int OUT, bool EDGE>
 __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
                                                  const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
+    // Tiles with few accumulators per lane fetch a contributor's whole share at once (one round trip
+    // per contributor instead of one per block and contributor); the big tiles have no registers for that.
+    constexpr bool WHOLE = C::ACC_REGS <= 64;
+    Acc sum[WHOLE ? C::MI : 1][WHOLE ? C::NI : 1];
+    if constexpr (WHOLE) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ni++) sum[mi][ni] = acc[mi][ni];
+        const float* src = part0;
+        for (int c = 0; c < n_contrib; c++) {
+            float v[C::ACC_REGS];
+#pragma unroll
+            for (int i = 0; i < C::ACC_REGS; i++)
+                v[i] = __hip_atomic_load(src + i * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+                for (int ni = 0; ni < C::NI; ni++)
+#pragma unroll
+                    for (int r = 0; r < C::ACC; r++) sum[mi][ni][r] += v[(mi * C::NI + ni) * C::ACC + r];
+            src += C::BM * C::BN;
+        }
+    }
 #pragma unroll
     for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++) {
-            Acc blk = acc[mi][ni];
-            const float* src = part0 + ((mi * C::NI + ni) * C::ACC) * C::THREADS;
-            for (int c = 0; c < n_contrib; c++) {
-                float v[C::ACC];
+            Acc blk;
+            if constexpr (WHOLE) {
+                blk = sum[mi][ni];
+            } else {
+                blk = acc[mi][ni];
+                const float* src = part0 + ((mi * C::NI + ni) * C::ACC) * C::THREADS;
+                for (int c = 0; c < n_contrib; c++) {
+                    float v[C::ACC];
 #pragma unroll
-                for (int r = 0; r < C::ACC; r++)
-                    v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int r = 0; r < C::ACC; r++)
+                        v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-                for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
-                src += C::BM * C::BN;
+                    for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
+                    src += C::BM * C::BN;
+                }
             }
             const int col = col0 + ni * C::MF;
 #pragma unroll
@@ -553,7 +583,31 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
         }
 }
 
-template <class C, bool ALIGNED>
+// Atomic fix-up (Algorithm 1, lines 14-18): a segment that covers only part of the tile's
+// K-iterations adds its accumulators into the zero-initialised fp32 image with atomic adds; a
+// segment that covers the whole tile stores them.
+template <class C, bool EDGE>
+__device__ __forceinline__ void add_to_image(const GemmArgs& g, int row0, int col0, bool partial,
+                                             const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ni++) {
+            const int col = col0 + ni * C::MF;
+#pragma unroll
+            for (int r = 0; r < C::ACC; r++) {
+                const int row = row0 + mi * C::MF + (r / 4) * (4 * C::KG) + r % 4;
+                if (!EDGE || (row < g.M && col < g.N)) {
+                    float* p = g.image + (size_t)((uint32_t)row * (uint32_t)g.N + (uint32_t)col);
+                    if (partial) unsafeAtomicAdd(p, acc[mi][ni][r]);
+                    else *p = acc[mi][ni][r];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+}
+
+template <class C, bool ALIGNED, bool ATOMIC = false>
 __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     extern __shared__ __align__(1024) unsigned char smem[];
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
@@ -605,6 +659,15 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
         mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, acc);
 
+        if (ATOMIC) {
+            int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
+            asm volatile("" : "+v"(row0), "+v"(col0));
+            const bool partial = k_begin > 0 || k_end < g.ipt;
+            if (m0 + C::BM > g.M || n0 + C::BN > g.N) add_to_image<C, true>(g, row0, col0, partial, acc);
+            else add_to_image<C, false>(g, row0, col0, partial, acc);
+            continue;
+        }
+
         // ---- fix-up
         // (the empty asm statements keep the per-block addresses from being computed once, ahead
         // of the persistent loop, where they would occupy registers for the whole kernel)
@@ -637,12 +700,19 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             // last iteration.  Wait for all of them; the epilogue adds their partials in a fixed
             // order, so the result does not depend on timing.
             const int last = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
-            if (tid == 0) {
+            if (wave == 0) {
+                // the lanes of the first wave watch up to 64 flags at a time, one flag each, so the
+                // wait costs one round trip however many contributors there are
                 uint32_t polls = 0;
-                for (int c = x + 1; c <= last; c++) {
-                    while (__hip_atomic_load(g.flags + (size_t)c * (SK_FLAG_STRIDE / 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != g.epoch) {
+                for (int base = x + 1; base <= last; base += 64) {
+                    const int c = base + lane <= last ? base + lane : last;
+                    const uint32_t* flag = g.flags + (size_t)c * (SK_FLAG_STRIDE / 4);
+                    bool seen = false;
+                    while (true) {
+                        if (!seen) seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.epoch;
+                        if (__all(seen)) break;
                         if (polls++ >= g.spin_limit) {   // bounded wait: record and go on
-                            __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (lane == 0) __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
                         __builtin_amdgcn_s_sleep(2);
@@ -675,35 +745,38 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
 // ---- kernel table entries --------------------------------------------------------------------
 typedef void (*kernel_fn)(GemmArgs);
 struct KernelEntry {
-    int dtype, bm, bn, bk, variant;
+    int dtype, bm, bn, bk, variant, fixup;
     kernel_fn aligned, generic;
     int threads, lds_bytes, piece_elems;
     std::atomic<int> max_resident{-1};   // co-resident workgroups on the device, -1 = not yet asked
-    KernelEntry(int d, int m, int n, int k, int v, kernel_fn a, kernel_fn g, int t, int l, int pe)
-        : dtype(d), bm(m), bn(n), bk(k), variant(v), aligned(a), generic(g), threads(t), lds_bytes(l), piece_elems(pe) {}
+    KernelEntry(int d, int m, int n, int k, int v, int fx, kernel_fn a, kernel_fn g, int t, int l, int pe)
+        : dtype(d), bm(m), bn(n), bk(k), variant(v), fixup(fx), aligned(a), generic(g), threads(t), lds_bytes(l), piece_elems(pe) {}
 };
 
-template <class C> KernelEntry* make_entry(int variant = 0) {
-    return new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, streamk_gemm_kernel<C, true>, streamk_gemm_kernel<C, false>,
+template <class C, bool ATOMIC = false> KernelEntry* make_entry(int variant = 0) {
+    return new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, ATOMIC ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS,
+                           streamk_gemm_kernel<C, true, ATOMIC>, streamk_gemm_kernel<C, false, ATOMIC>,
                            C::THREADS, C::LDS_BYTES, C::PE);
 }
 
 // Tile shapes with a kernel: <dtype, BM, BN, BK, waves along M, waves along N, matrix-core block,
 // A ring depth[, B ring depth]>.  Variant 0 of a shape is the one sk_gemm uses; other variants are
 // alternative wave layouts / ring depths of the same shape, selectable with the environment
-// variable SK_KERNEL_VARIANT for tuning runs.
-template <int DT> void add_16bit_tiles(KernelEntry** t, int* n) {
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 2, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>(1);
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2>>(1);
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 2, 2>>(2);
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>>();
-    t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>>();
+// variable SK_KERNEL_VARIANT for tuning runs.  ATOMIC selects the atomic-add fix-up (sk_fixup).
+template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int* n) {
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 2, 32, 4>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>, ATOMIC>();
+    if constexpr (!ATOMIC) {  // (the atomic fix-up exists for the layouts above only)
+        t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 2, 2>>(2);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
+    }
 }
 
 // One function per input type, each in its own translation unit (so that they compile in parallel);
@@ -711,5 +784,8 @@ template <int DT> void add_16bit_tiles(KernelEntry** t, int* n) {
 void register_bf16(KernelEntry** t, int* n);
 void register_f16(KernelEntry** t, int* n);
 void register_fp8(KernelEntry** t, int* n);
+void register_bf16_atomic(KernelEntry** t, int* n);
+void register_f16_atomic(KernelEntry** t, int* n);
+void register_fp8_atomic(KernelEntry** t, int* n);
 
 }  // namespace streamk_detail

@@ -228,7 +228,14 @@ extern "C" int bloom_shape_key(const sk_plan_t* plan, uint32_t* key) {
 extern "C" size_t sk_workspace_bytes(const sk_plan_t* plan) {
     if (!plan) return 0;
     const sk_plan_header& h = plan->h;
+    if (plan->fixup == SK_FIXUP_ATOMIC) return sk_ws_partials_offset(h.grid) + sk_ws_image_bytes(plan);
     return sk_ws_partials_offset(h.grid) + (size_t)h.grid * h.blk_m * h.blk_n * sizeof(float);
+}
+
+extern "C" int sk_plan_set_fixup(sk_plan_t* plan, int fixup) {
+    if (!plan || (fixup != SK_FIXUP_FLAGS && fixup != SK_FIXUP_ATOMIC) || plan->workspace) return SK_ERR_INVALID_ARG;
+    plan->fixup = fixup;
+    return SK_OK;
 }
 
 extern "C" int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls) {

@@ -19,17 +19,20 @@ TOL_16, TOL_32 = 1e-2, 1e-4
 ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16, inputs.E4M3: G.E4M3}
 
 
-def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False):
+def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False,
+                     fixup=sk.SK_FIXUP_FLAGS, launches=1):
     M, K = A.shape
     N = B.shape[1]
-    print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s" %
-          (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype), flush=True)
-    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype)
+    print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s fixup=%d" %
+          (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype, fixup), flush=True)
+    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup)
     try:
         # the library's schedule for this very launch equals the oracle's
         o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"], r.info["tile_order"])
         assert sk.sk_plan_segments(r.plan) == [tuple(s) for s in o.segments]
-        r.run(to_device(A), to_device(B))
+        dA, dB = to_device(A), to_device(B)
+        for _ in range(launches):
+            r.run(dA, dB)
         assert r.check() == sk.SK_OK
         d = r.result()
     finally:
@@ -175,3 +178,53 @@ def test_config5_large_square_fp8_sampled_rows():
     ref = G.gemm_fp64(c["A"], c["B"], G.E4M3, rows=rows)
     for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK3_DP, sk.SK_POLICY_ALL_SK):
         _run_and_compare(c["A"], c["B"], inputs.E4M3, policy, None, 256, rows=rows, ref=ref)
+
+
+# ---- atomic-add fix-up (Algorithm 1, lines 14-18): same schedules, partial tiles added into a zeroed fp32 image
+
+@pytest.mark.parametrize("blk", [t[:3] for t in TILES])
+def test_atomic_fixup_integer_inputs_bit_exact(blk):
+    # integer-valued inputs: every summation order gives the same fp32 result, so the comparison is exact
+    # although the order of the atomic adds is not fixed; two launches in a row: the image is cleared each time
+    M, N, K = 2 * blk[0] + 40, 3 * blk[1] + 72, 5 * blk[2] + 24
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 22)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for policy in (0, 1, 2, 6):
+        _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True,
+                         fixup=sk.SK_FIXUP_ATOMIC, launches=2)
+
+
+@pytest.mark.parametrize("policy", range(7))
+def test_atomic_fixup_config1_fp16(policy):
+    # 16-bit output goes through the fp32 image in the workspace and the conversion kernel
+    c = inputs.config1()
+    ref = G.gemm_fp64(c["A"], c["B"], G.F16)
+    _run_and_compare(c["A"], c["B"], inputs.F16, policy, c["blk"], c["grid"], ref=ref, fixup=sk.SK_FIXUP_ATOMIC, launches=2)
+    _run_and_compare(c["A"], c["B"], inputs.F16, policy, c["blk"], c["grid"], out_dtype=sk.SK_F32, ref=ref,
+                     fixup=sk.SK_FIXUP_ATOMIC)
+
+
+@pytest.mark.parametrize("shape", [(77, 101, 203), (1, 64, 16), (130, 129, 1), (300, 8, 2049), (333, 515, 777)])
+def test_atomic_fixup_ragged_shapes(shape):
+    M, N, K = shape
+    A, B = inputs.uniform_pair(M, N, K, inputs.BF16, 9)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for policy in (1, 6):
+        _run_and_compare(A, B, inputs.BF16, policy, None, grid=256, ref=ref, fixup=sk.SK_FIXUP_ATOMIC)
+        _run_and_compare(A, B, inputs.BF16, policy, None, grid=40, out_dtype=sk.SK_F32, ref=ref, fixup=sk.SK_FIXUP_ATOMIC)
+
+
+def test_atomic_fixup_fp8_and_unsupported_tile():
+    blk = (128, 256, 128)
+    M, N, K = 2 * blk[0] + 40, 2 * blk[1] + 72, 5 * blk[2] + 24
+    A, B = inputs.small_int_pair(M, N, K, inputs.E4M3, 5)
+    ref = G.gemm_fp64(A, B, G.E4M3)
+    _run_and_compare(A, B, inputs.E4M3, 6, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True, fixup=sk.SK_FIXUP_ATOMIC)
+    # a tile shape without an atomic kernel is refused, not run some other way
+    r = Runner(600, 600, 600, 6, (256, 256, 32), 24, sk.SK_BF16, sk.SK_F32, fixup=sk.SK_FIXUP_ATOMIC)
+    try:
+        a = torch.zeros((600, 600), dtype=torch.int16, device="cuda")
+        st = sk.sk_gemm_status(a.data_ptr(), a.data_ptr(), r.D.data_ptr(), r.plan, torch.cuda.current_stream().cuda_stream)
+        assert st == sk.SK_ERR_UNSUPPORTED
+    finally:
+        r.close()

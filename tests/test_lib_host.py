@@ -109,6 +109,28 @@ def test_gemm_rejects_bad_arguments_without_touching_the_gpu():
     sk.sk_plan_destroy(p)
 
 
+def test_fixup_mode_setter_and_workspace_need():
+    import ctypes
+    lib = sk.binding._lib
+    p = sk.sk_plan(512, 384, 512, sk.SK_POLICY_ALL_SK, (128, 128, 32), 256, sk.SK_F16)
+    flags_bytes = sk.sk_workspace_bytes(p)
+    assert flags_bytes >= 256 * 128 * 128 * 4
+    assert lib.sk_plan_set_fixup(p, 2) == sk.SK_ERR_INVALID_ARG
+    assert lib.sk_plan_set_fixup(None, 0) == sk.SK_ERR_INVALID_ARG
+    sk.sk_plan_set_fixup(p, sk.SK_FIXUP_ATOMIC)
+    # atomic mode with a 16-bit output: flag / status lines + an fp32 image of D
+    assert sk.sk_workspace_bytes(p) == flags_bytes - 256 * 128 * 128 * 4 + 512 * 384 * 4
+    assert sk.sk_gemm_status(256, 512, 768, p) == sk.SK_ERR_WORKSPACE            # image lives in the workspace
+    sk.sk_plan_set_fixup(p, sk.SK_FIXUP_FLAGS)
+    assert sk.sk_workspace_bytes(p) == flags_bytes
+    sk.sk_plan_destroy(p)
+    # fp32 output: D itself is accumulated into, no image in the workspace
+    p = sk.sk_plan(512, 384, 512, sk.SK_POLICY_ALL_SK, (128, 128, 32), 256, sk.SK_F16, sk.SK_F32)
+    sk.sk_plan_set_fixup(p, sk.SK_FIXUP_ATOMIC)
+    assert sk.sk_workspace_bytes(p) == flags_bytes - 256 * 128 * 128 * 4
+    sk.sk_plan_destroy(p)
+
+
 # ---- Bloom -----------------------------------------------------------------------------------
 
 def test_hash_bit_exact_with_oracle():
