@@ -532,20 +532,30 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
             for (int ni = 0; ni < C::NI; ni++) sum[mi][ni] = acc[mi][ni];
+        // G contributors per round trip (about 64 registers of loads in flight); the additions keep
+        // the ascending contributor order
+        constexpr int G = 64 / C::ACC_REGS < 8 ? 64 / C::ACC_REGS : 8;
+        auto add_group = [&](const float* src, auto count) {
+            constexpr int CNT = decltype(count)::value;
+            float v[CNT][C::ACC_REGS];
+#pragma unroll
+            for (int j = 0; j < CNT; j++)
+#pragma unroll
+                for (int i = 0; i < C::ACC_REGS; i++)
+                    v[j][i] = __hip_atomic_load(src + (size_t)j * (C::BM * C::BN) + i * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int j = 0; j < CNT; j++)
+#pragma unroll
+                for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+                    for (int ni = 0; ni < C::NI; ni++)
+#pragma unroll
+                        for (int r = 0; r < C::ACC; r++) sum[mi][ni][r] += v[j][(mi * C::NI + ni) * C::ACC + r];
+        };
         const float* src = part0;
-        for (int c = 0; c < n_contrib; c++) {
-            float v[C::ACC_REGS];
-#pragma unroll
-            for (int i = 0; i < C::ACC_REGS; i++)
-                v[i] = __hip_atomic_load(src + i * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-                for (int ni = 0; ni < C::NI; ni++)
-#pragma unroll
-                    for (int r = 0; r < C::ACC; r++) sum[mi][ni][r] += v[(mi * C::NI + ni) * C::ACC + r];
-            src += C::BM * C::BN;
-        }
+        int c = 0;
+        for (; c + G <= n_contrib; c += G, src += (size_t)G * (C::BM * C::BN)) add_group(src, std::integral_constant<int, G>());
+        for (; c < n_contrib; c++, src += C::BM * C::BN) add_group(src, std::integral_constant<int, 1>());
     }
 #pragma unroll
     for (int mi = 0; mi < C::MI; mi++)

@@ -147,6 +147,21 @@ def sweep_statistics(records):
     for tol in (0.0, 0.05, 0.1, 0.2):
         out["share_stream_k_within_%g_of_dp" % tol] = sum(
             min(r["time_ns"][1:]) * 1000 <= r["time_ns"][0] * (1000 + int(tol * 1000)) for r in records) / n
+    # per winning policy: by how much it beats the runner-up, the best *different* schedule
+    # (policies with the same number of Stream-K tiles are one schedule), in the style of Sec. 5.2
+    margins = [[] for _ in range(N_POL)]
+    for r in records:
+        t = r["time_ns"]
+        w = t.index(min(t))
+        others = [t[q] for q in range(N_POL) if r["sk_tiles"][q] != r["sk_tiles"][w]]
+        if others:
+            margins[w].append(min(others) / t[w] - 1)
+    out["gain_over_runner_up"] = {}
+    for p in range(N_POL):
+        m = sorted(margins[p])
+        if m:
+            out["gain_over_runner_up"][sk.POLICY_NAMES[p]] = {
+                "sizes": len(m), "median": m[len(m) // 2], "p90": m[min(len(m) - 1, (9 * len(m)) // 10)], "max": m[-1]}
     return out
 
 

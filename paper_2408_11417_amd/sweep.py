@@ -33,7 +33,7 @@ def time_policy(sk, torch, plan, dA, dB, dD, stream, est_ms):
     return e0.elapsed_time(e1) / reps, reps
 
 
-def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25):
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0):
     import torch
     import paper_2408_11417_amd as sk
 
@@ -58,6 +58,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25):
     pd = torch.empty(max_d, dtype=tdt, device="cuda")
     pd2 = torch.empty(max_d, dtype=tdt, device="cuda")
     ws_bytes = 256 * 256 * 256 * 4 + (1 << 16)
+    if fixup:                                  # the atomic fix-up keeps an fp32 image of D in the workspace
+        ws_bytes = max(ws_bytes, max_d * 4 + (1 << 16))
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
     ws_ptr = (ws.data_ptr() + 255) // 256 * 256
 
@@ -66,6 +68,7 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25):
         plans, infos = [], []
         for p in range(sk.SK_NUM_POLICIES):
             plan = sk.sk_plan(M, N, K, p, None, 256, dtype_code, dtype_code)
+            sk.sk_plan_set_fixup(plan, fixup)
             assert sk.sk_workspace_bytes(plan) <= ws_bytes
             sk.sk_plan_set_workspace(plan, ws_ptr, ws_bytes)
             plans.append(plan)
@@ -105,7 +108,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25):
                 sk.POLICY_NAMES[times.index(best)], 2.0 * M * N * K / best / 1e9, times[0]), flush=True)
         if out_path and (idx % 50 == 49 or idx == len(shapes) - 1):
             with open(out_path, "w") as f:
-                json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256, "records": records}, f)
+                json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256,
+                           "fixup": "atomic" if fixup else "flags", "records": records}, f)
     return records
 
 
@@ -115,12 +119,14 @@ def main():
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--out", default="sweep_bf16.json")
     ap.add_argument("--first", type=int, default=0, help="only the first N shapes (smoke runs)")
+    ap.add_argument("--fixup", choices=("flags", "atomic"), default="flags",
+                    help="how split tiles are combined (atomic = Algorithm 1, lines 14-18)")
     args = ap.parse_args()
     from paper_2408_11417_amd import inputs
     shapes = inputs.sweep_shapes(args.shapes, args.seed)
     if args.first:
         shapes = shapes[:args.first]
-    run(shapes, args.out)
+    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0)
     return 0
 
 

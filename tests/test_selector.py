@@ -77,3 +77,14 @@ def test_statistics_shape():
     st = selector.sweep_statistics(_fake_records(40, 9))
     assert abs(sum(st["winner_share"].values()) - 1.0) < 1e-9
     assert st["share_stream_k_within_0_of_dp"] <= st["share_stream_k_within_0.2_of_dp"] <= 1.0
+    g = st["gain_over_runner_up"]
+    assert sum(v["sizes"] for v in g.values()) <= 40
+    for v in g.values():
+        assert 0.0 <= v["median"] <= v["p90"] <= v["max"]
+
+
+def test_runner_up_margin_by_hand():
+    # two schedules (policies 1..6 share sk_tiles): DP 100, the Stream-K schedule 80 -> winner SK1_DP, margin 100/80 - 1
+    rec = {"M": 64, "N": 64, "K": 64, "tiles": 4, "sk_tiles": [0, 4, 4, 4, 4, 4, 4], "time_ns": [100, 80, 80, 80, 80, 80, 80]}
+    st = selector.sweep_statistics([rec])
+    assert st["gain_over_runner_up"] == {"SK1_DP": {"sizes": 1, "median": 0.25, "p90": 0.25, "max": 0.25}}
