@@ -191,15 +191,23 @@ int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls);
  * is one kernel.  With SK_FIXUP_ATOMIC and a plan that splits tiles it is a fill
  * kernel that zeroes the fp32 image, the GEMM kernel, and - for 16-bit outputs -
  * a conversion kernel from the fp32 image to D; plans without split tiles run
- * the same single kernel under both modes.
+ * the same single kernel under both modes.  No memset or copy node is enqueued
+ * and no kernel argument changes from launch to launch, so a launch captured
+ * into a HIP graph may be replayed (make one ordinary launch of the plan first:
+ * the first use of a kernel sets its LDS limit and asks for its occupancy, which
+ * capture does not allow).
  * Errors: INVALID_ARG, UNSUPPORTED (no kernel for tile + dtype, or the grid
  * cannot be co-resident while the plan has split tiles), WORKSPACE (plan has
  * split tiles but no workspace), HIP (launch failed). */
 int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream);
 
-/* Blocking: waits for `stream`, reads the workspace status word and clears it.
- * Returns SK_OK, or SK_ERR_TIMEOUT if any launch since the last check gave up
- * waiting for a partial tile. */
+/* Blocking: waits for `stream` and reads the workspace status word.  Returns
+ * SK_OK, or SK_ERR_TIMEOUT if any launch since the last check gave up waiting
+ * for a partial tile; in that case the flag and status area is cleared, so the
+ * workspace can be used again.  (Flags are raised by contributors and taken
+ * down by the owner that waits for them inside the same launch; after a
+ * time-out some may be left up, and launches made before this call returns
+ * would read partial tiles too early.) */
 int sk_plan_check(const sk_plan_t* plan, void* stream);
 
 void sk_plan_destroy(sk_plan_t* plan);

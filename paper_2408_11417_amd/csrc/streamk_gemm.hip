@@ -39,7 +39,6 @@ KernelEntry* find_kernel(int dtype, int bm, int bn, int bk, int fixup = SK_FIXUP
     return fallback;
 }
 
-std::atomic<uint32_t> g_epoch{0};
 
 // Helpers of the atomic fix-up: clear the fp32 image, and turn it into a 16-bit D afterwards.
 __global__ void zero_image_kernel(float4* p, size_t n4, float* tail, int n_tail) {
@@ -87,7 +86,8 @@ extern "C" int sk_plan_check(const sk_plan_t* plan, void* stream) {
     uint32_t v = 0;
     if (!hip_ok(hipMemcpy(&v, st, sizeof v, hipMemcpyDeviceToHost))) return SK_ERR_HIP;
     if (v) {
-        if (!hip_ok(hipMemset(st, 0, sizeof v))) return SK_ERR_HIP;
+        // flags of contributors that nobody waited for may still be up: take the whole flag and status area down
+        if (!hip_ok(hipMemset(plan->workspace, 0, sk_ws_partials_offset(plan->h.grid)))) return SK_ERR_HIP;
         return SK_ERR_TIMEOUT;
     }
     return SK_OK;
@@ -134,9 +134,6 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.M = (int)h.M; g.N = (int)h.N; g.K = (int)h.K;
     g.tiles_m = h.tiles_m; g.tiles_n = h.tiles_n; g.tiles = h.tiles; g.ipt = h.iters_per_tile; g.tile_order = h.tile_order;
     g.sk_tiles = h.sk_tiles; g.ipw = h.iters_per_wg; g.grid = h.grid; g.sk_iters = (int)h.sk_iters;
-    uint32_t ep = ++g_epoch;
-    if (ep == 0) ep = ++g_epoch;                 // 0 is the cleared state of a flag
-    g.epoch = ep;
     g.spin_limit = plan->spin_limit;
     g.out_dtype = h.out_dtype;
     if (atomic) {

@@ -42,7 +42,7 @@ struct GemmArgs {
     uint32_t* status;      // set non-zero when an owner gives up waiting
     int M, N, K;
     int tiles_m, tiles_n, tiles, ipt, sk_tiles, ipw, grid, sk_iters, tile_order;
-    uint32_t epoch, spin_limit;
+    uint32_t spin_limit;
     int out_dtype;
 };
 
@@ -701,7 +701,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             wait_vmcnt<0>();                      // every lane's part of the partial tile has reached memory
             __syncthreads();
             if (tid == 0)
-                __hip_atomic_store(g.flags + (size_t)x * (SK_FLAG_STRIDE / 4), g.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(g.flags + (size_t)x * (SK_FLAG_STRIDE / 4), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             continue;
         }
         int n_contrib = 0;
@@ -712,14 +712,20 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             const int last = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
             if (wave == 0) {
                 // the lanes of the first wave watch up to 64 flags at a time, one flag each, so the
-                // wait costs one round trip however many contributors there are
+                // wait costs one round trip however many contributors there are.  A lane that has
+                // seen its flag takes it down again: every flag is watched by exactly one lane of
+                // one owner, so all flags are back at zero when the kernel ends and the next
+                // launch (or a replay of a captured launch) starts from the same state.
                 uint32_t polls = 0;
                 for (int base = x + 1; base <= last; base += 64) {
-                    const int c = base + lane <= last ? base + lane : last;
-                    const uint32_t* flag = g.flags + (size_t)c * (SK_FLAG_STRIDE / 4);
-                    bool seen = false;
+                    const bool mine = base + lane <= last;
+                    uint32_t* flag = g.flags + (size_t)(mine ? base + lane : last) * (SK_FLAG_STRIDE / 4);
+                    bool seen = !mine;
                     while (true) {
-                        if (!seen) seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.epoch;
+                        if (!seen && __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                            seen = true;
+                            __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
                         if (__all(seen)) break;
                         if (polls++ >= g.spin_limit) {   // bounded wait: record and go on
                             if (lane == 0) __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -228,3 +228,32 @@ def test_atomic_fixup_fp8_and_unsupported_tile():
         assert st == sk.SK_ERR_UNSUPPORTED
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("fixup", [sk.SK_FIXUP_FLAGS, sk.SK_FIXUP_ATOMIC])
+def test_hip_graph_replay_matches_eager(fixup):
+    # a captured launch holds no memset node and no per-launch argument: replays, with eager work and
+    # synchronisations in between, must give the eager result every time (integer inputs: exact under both fix-ups)
+    M = N = K = 512
+    A, B = inputs.small_int_pair(M, N, K, inputs.F16, 31)
+    dA, dB = to_device(A), to_device(B)
+    r = Runner(M, N, K, sk.SK_POLICY_ALL_SK, (128, 128, 32), 256, inputs.F16, sk.SK_F32, fixup=fixup)
+    try:
+        eager = r.run(dA, dB).clone()            # also the first use of the kernel (not allowed under capture)
+        assert r.check() == sk.SK_OK
+        assert np.array_equal(eager.cpu().numpy().astype(np.float64), G.gemm_fp64(A, B, G.F16))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            r.run(dA, dB)
+        for i in range(6):
+            r.D.fill_(-1.0)                      # eager work between the replays
+            if i % 2:
+                assert torch.equal(r.run(dA, dB), eager)   # and eager launches of the same plan
+                r.D.fill_(-2.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(r.D, eager), "replay %d differs" % i
+        assert r.check() == sk.SK_OK
+    finally:
+        r.close()
