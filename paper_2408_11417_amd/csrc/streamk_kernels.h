@@ -29,6 +29,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
@@ -47,9 +49,14 @@ struct GemmArgs {
 };
 
 // ---- matrix-core wrappers ---------------------------------------------------------------------
-// One instruction multiplies an MF x KM block of A by a KM x MF block of B.  Lane l holds, for A,
-// row l % MF and the 8 consecutive k starting at 8 * (l / MF); for B, column l % MF and the same
-// k; for the MF x MF result, column l % MF and rows (r/4) * (256/MF) + 4 * (l / MF) + r % 4.
+// One instruction multiplies an MF x KM block (first operand) by a KM x MF block (second operand).
+// Lane l holds, for the first operand, row l % MF and the 8 consecutive k starting at
+// 8 * (l / MF); for the second, column l % MF and the same k; for the MF x MF result, column
+// l % MF and rows (r/4) * (256/MF) + 4 * (l / MF) + r % 4.  Both operands have the same register
+// format, so the kernels pass the B block first and the A block second: the instruction then
+// produces the transposed block, i.e. lane l holds row l % MF of the D block and, in registers
+// 4q .. 4q+3, the four consecutive columns (256/MF) * q + 4 * (l / MF) + {0..3}, which can be
+// stored as vectors.
 template <int DT, int MF> struct Mfma;
 template <> struct Mfma<SK_BF16, 32> {
     typedef f32x16 Acc;
@@ -393,7 +400,7 @@ __device__ __forceinline__ void mma_step(const Frags<C>& f, typename Mfma<C::DT,
     for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++)
-            acc[mi][ni] = Mfma<C::DT, C::MF>::run(f.a[mi], f.b[ni], acc[mi][ni]);
+            acc[mi][ni] = Mfma<C::DT, C::MF>::run(f.b[ni], f.a[mi], acc[mi][ni]);   // transposed product, see Mfma
 }
 
 // All k-steps of one stage, for the register-staged path: the operands of step kk+1 are read from
@@ -515,11 +522,77 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
     }
 }
 
-// Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): per accumulator block, add the
-// parked partials of the contributors in ascending workgroup order (= ascending k), convert and
-// store.  OUT selects the output type, EDGE adds the bounds checks.  The big tiles work one block at
-// a time, which keeps their register need flat.
-template <class C, int OUT, bool EDGE>
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return (uint32_t)to_bf16_bits(lo) | ((uint32_t)to_bf16_bits(hi) << 16); }
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+    return (uint32_t)__builtin_bit_cast(u16, (_Float16)lo) | ((uint32_t)__builtin_bit_cast(u16, (_Float16)hi) << 16);
+}
+
+// Convert and store one accumulator block.  Lane l holds row `row` (= block row l % MF) and in
+// registers 4q..4q+3 the columns col0 + 4*KG*q + {0..3}, col0 already including 4 * (l / MF).
+// VEC (rows of D start on 16-byte boundaries and N is a multiple of 8): 16-bit outputs of the
+// 32 x 32 block exchange register pairs between lanes l and l + 32, after which a lane owns 8
+// consecutive columns = one 16-byte store; fp32 outputs store 4 columns = 16 bytes per q.  A
+// group of 4 (8) columns starting at a multiple of 4 (8) is then inside N as a whole or not at all.
+template <class C, int OUT, bool EDGE, bool VEC>
+__device__ __forceinline__ void store_block(const GemmArgs& g, int row, int col0, const typename Mfma<C::DT, C::MF>::Acc& blk) {
+    constexpr int Q = C::ACC / 4, QS = 4 * C::KG;    // column groups per lane, distance between them
+    const bool row_ok = !EDGE || row < g.M;
+    const uint32_t row_off = (uint32_t)row * (uint32_t)g.N;
+    if constexpr (!VEC) {
+#pragma unroll
+        for (int r = 0; r < C::ACC; r++) {
+            const int col = col0 + (r / 4) * QS + r % 4;
+            if (row_ok && (!EDGE || col < g.N)) {
+                const size_t o = (size_t)(row_off + (uint32_t)col);
+                if (OUT == SK_F32) static_cast<float*>(g.D)[o] = blk[r];
+                else if (OUT == SK_BF16) static_cast<u16*>(g.D)[o] = to_bf16_bits(blk[r]);
+                else static_cast<_Float16*>(g.D)[o] = (_Float16)blk[r];
+            }
+        }
+    } else if constexpr (OUT == SK_F32) {
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            const int col = col0 + q * QS;
+            if (row_ok && (!EDGE || col < g.N))
+                *reinterpret_cast<f32x4*>(static_cast<float*>(g.D) + (size_t)(row_off + (uint32_t)col)) =
+                    f32x4{blk[4 * q], blk[4 * q + 1], blk[4 * q + 2], blk[4 * q + 3]};
+        }
+    } else {
+        uint32_t w[Q][2];
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            w[q][0] = OUT == SK_BF16 ? pack_bf16(blk[4 * q], blk[4 * q + 1]) : pack_f16(blk[4 * q], blk[4 * q + 1]);
+            w[q][1] = OUT == SK_BF16 ? pack_bf16(blk[4 * q + 2], blk[4 * q + 3]) : pack_f16(blk[4 * q + 2], blk[4 * q + 3]);
+        }
+        if constexpr (C::MF == 32) {
+            // groups q (lanes below 32 keep theirs) and q + 1 (lanes from 32 up keep theirs): after the
+            // exchange a lane holds columns 8 * (q + l / 32) .. + 7 of its row, relative to the block
+            const int half = threadIdx.x % 64 / 32;
+#pragma unroll
+            for (int q = 0; q < Q; q += 2) {
+                const u32x2 d0 = __builtin_amdgcn_permlane32_swap(w[q][0], w[q + 1][0], false, false);
+                const u32x2 d1 = __builtin_amdgcn_permlane32_swap(w[q][1], w[q + 1][1], false, false);
+                const int col = col0 - 4 * half + 8 * (q + half);
+                if (row_ok && (!EDGE || col < g.N))
+                    *reinterpret_cast<u32x4*>(static_cast<u16*>(g.D) + (size_t)(row_off + (uint32_t)col)) = u32x4{d0[0], d1[0], d0[1], d1[1]};
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                const int col = col0 + q * QS;
+                if (row_ok && (!EDGE || col < g.N))
+                    *reinterpret_cast<u32x2*>(static_cast<u16*>(g.D) + (size_t)(row_off + (uint32_t)col)) = u32x2{w[q][0], w[q][1]};
+            }
+        }
+    }
+}
+
+// Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): add the parked partials of the
+// contributors in ascending workgroup order (= ascending k), convert and store.  OUT selects the
+// output type, EDGE adds the bounds checks, VEC the vector stores.  row0 / col0: the lane's row and
+// first column in the wave's first block.  The big tiles work one block at a time, which keeps
+// their register need flat.
+template <class C, int OUT, bool EDGE, bool VEC>
 __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
                                                  const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
@@ -577,25 +650,14 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
                     src += C::BM * C::BN;
                 }
             }
-            const int col = col0 + ni * C::MF;
-#pragma unroll
-            for (int r = 0; r < C::ACC; r++) {
-                const int row = row0 + mi * C::MF + (r / 4) * (4 * C::KG) + r % 4;
-                if (!EDGE || (row < g.M && col < g.N)) {
-                    const size_t o = (size_t)((uint32_t)row * (uint32_t)g.N + (uint32_t)col);
-                    const float v = blk[r];
-                    if (OUT == SK_F32) static_cast<float*>(g.D)[o] = v;
-                    else if (OUT == SK_BF16) static_cast<u16*>(g.D)[o] = to_bf16_bits(v);
-                    else static_cast<_Float16*>(g.D)[o] = (_Float16)v;
-                }
-            }
+            store_block<C, OUT, EDGE, VEC>(g, row0 + mi * C::MF, col0 + ni * C::MF, blk);
             __builtin_amdgcn_sched_barrier(0);
         }
 }
 
 // Atomic fix-up (Algorithm 1, lines 14-18): a segment that covers only part of the tile's
 // K-iterations adds its accumulators into the zero-initialised fp32 image with atomic adds; a
-// segment that covers the whole tile stores them.
+// segment that covers the whole tile stores them.  row0 / col0 as in reduce_and_store.
 template <class C, bool EDGE>
 __device__ __forceinline__ void add_to_image(const GemmArgs& g, int row0, int col0, bool partial,
                                              const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
@@ -603,10 +665,10 @@ __device__ __forceinline__ void add_to_image(const GemmArgs& g, int row0, int co
     for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++) {
-            const int col = col0 + ni * C::MF;
+            const int row = row0 + mi * C::MF;
 #pragma unroll
             for (int r = 0; r < C::ACC; r++) {
-                const int row = row0 + mi * C::MF + (r / 4) * (4 * C::KG) + r % 4;
+                const int col = col0 + ni * C::MF + (r / 4) * (4 * C::KG) + r % 4;
                 if (!EDGE || (row < g.M && col < g.N)) {
                     float* p = g.image + (size_t)((uint32_t)row * (uint32_t)g.N + (uint32_t)col);
                     if (partial) unsafeAtomicAdd(p, acc[mi][ni][r]);
@@ -670,7 +732,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, acc);
 
         if (ATOMIC) {
-            int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
+            int row0 = m0 + wm * C::WTM + lane % C::MF, col0 = n0 + wn * C::WTN + 4 * (lane / C::MF);
             asm volatile("" : "+v"(row0), "+v"(col0));
             const bool partial = k_begin > 0 || k_end < g.ipt;
             if (m0 + C::BM > g.M || n0 + C::BN > g.N) add_to_image<C, true>(g, row0, col0, partial, acc);
@@ -740,20 +802,20 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         }
 
         // ---- epilogue: fp32 accumulators -> D
-        int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
+        int row0 = m0 + wm * C::WTM + lane % C::MF, col0 = n0 + wn * C::WTN + 4 * (lane / C::MF);
         asm volatile("" : "+v"(row0), "+v"(col0));
         const float* part0 = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
         asm volatile("" : "+v"(part0));
         const bool edge = m0 + C::BM > g.M || n0 + C::BN > g.N;
         if (g.out_dtype == SK_BF16) {
-            if (edge) reduce_and_store<C, SK_BF16, true>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_BF16, false>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_BF16, true, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_BF16, false, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
         } else if (g.out_dtype == SK_F16) {
-            if (edge) reduce_and_store<C, SK_F16, true>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F16, false>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_F16, true, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_F16, false, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
         } else {
-            if (edge) reduce_and_store<C, SK_F32, true>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F32, false>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_F32, true, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_F32, false, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
         }
     }
 }
