@@ -394,18 +394,19 @@ template <class C, int LATER> __device__ __forceinline__ void wait_stage(int lat
 }
 
 // The matrix-core work of one k-step.
-template <class C>
+// TR: pass the B block first and the A block second, which yields the transposed result block.
+template <class C, bool TR>
 __device__ __forceinline__ void mma_step(const Frags<C>& f, typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
 #pragma unroll
     for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++)
-            acc[mi][ni] = Mfma<C::DT, C::MF>::run(f.b[ni], f.a[mi], acc[mi][ni]);   // transposed product, see Mfma
+            acc[mi][ni] = TR ? Mfma<C::DT, C::MF>::run(f.b[ni], f.a[mi], acc[mi][ni]) : Mfma<C::DT, C::MF>::run(f.a[mi], f.b[ni], acc[mi][ni]);
 }
 
 // All k-steps of one stage, for the register-staged path: the operands of step kk+1 are read from
 // LDS while the matrix cores work on step kk.
-template <class C>
+template <class C, bool TR>
 __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm,
                                           typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     Frags<C> f[2];
@@ -413,7 +414,7 @@ __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const un
 #pragma unroll
     for (int kk = 0; kk < C::KK; kk++) {
         if (kk + 1 < C::KK) f[(kk + 1) & 1].load(a_stage, b_stage, fm, kk + 1);
-        mma_step<C>(f[kk & 1], acc);
+        mma_step<C, TR>(f[kk & 1], acc);
     }
 }
 
@@ -425,7 +426,7 @@ __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const un
 // so (1) stage i's slots can be refilled at once (with stages i+NSB / i+NSA), (2) the operands of
 // stage i+1's first k-step are read while the matrix cores still work on stage i's last one, and
 // (3) the time a wave spends at the barrier is covered by matrix-core work already queued.
-template <class C, bool ALIGNED>
+template <class C, bool ALIGNED, bool TR>
 __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int k_begin, int k_end,
                                          unsigned char* smem, const FragMap<C>& fm,
                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
@@ -483,7 +484,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
             }
             issue_batch(i, ca, cb, 0, C::KK);
             if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
-            if (!FIRST) mma_step<C>(f[1], acc);          // last k-step of stage i
+            if (!FIRST) mma_step<C, TR>(f[1], acc);          // last k-step of stage i
             if (has_next) {
 #pragma unroll
                 for (int kk = 0; kk < C::KK - 1; kk++) {
@@ -491,7 +492,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
                     f[(kk + 1) & 1].load(a_next, b_next, fm, kk + 1);
                     issue_batch(i, ca, cb, kk + 1, C::KK);
                     if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
-                    mma_step<C>(f[kk & 1], acc);
+                    mma_step<C, TR>(f[kk & 1], acc);
                 }
             }
             ca = na;
@@ -516,7 +517,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
             unsigned char* b_stage = smem + C::B_RING + slot * C::B_BYTES;
             fill_stage_staged<C, ALIGNED>(g, m0, n0, k, a_stage, b_stage);
             __syncthreads();
-            mac_stage<C>(a_stage, b_stage, fm, acc);
+            mac_stage<C, TR>(a_stage, b_stage, fm, acc);
         }
         __syncthreads();
     }
@@ -527,29 +528,35 @@ __device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
     return (uint32_t)__builtin_bit_cast(u16, (_Float16)lo) | ((uint32_t)__builtin_bit_cast(u16, (_Float16)hi) << 16);
 }
 
-// Convert and store one accumulator block.  Lane l holds row `row` (= block row l % MF) and in
-// registers 4q..4q+3 the columns col0 + 4*KG*q + {0..3}, col0 already including 4 * (l / MF).
-// VEC (rows of D start on 16-byte boundaries and N is a multiple of 8): 16-bit outputs of the
-// 32 x 32 block exchange register pairs between lanes l and l + 32, after which a lane owns 8
-// consecutive columns = one 16-byte store; fp32 outputs store 4 columns = 16 bytes per q.  A
-// group of 4 (8) columns starting at a multiple of 4 (8) is then inside N as a whole or not at all.
-template <class C, int OUT, bool EDGE, bool VEC>
+// Convert and store one accumulator block.
+// TR (transposed blocks; used when rows of D start on 16-byte boundaries and N is a multiple of 8):
+// lane l holds row `row` (= block row l % MF) and in registers 4q..4q+3 the columns
+// col0 + 4*KG*q + {0..3}, col0 already including 4 * (l / MF).  16-bit outputs of the 32 x 32 block
+// exchange register pairs between lanes l and l + 32, after which a lane owns 8 consecutive columns
+// = one 16-byte store; fp32 outputs store 4 columns = 16 bytes per q.  A group of 4 (8) columns
+// starting at a multiple of 4 (8) is then inside N as a whole or not at all.
+// Not TR: lane l holds column `col0` (= block column l % MF) and in register r the row
+// row + 4*KG*(r/4) + r%4, `row` already including 4 * (l / MF); stored element by element, the
+// lanes of one store instruction side by side in a row of D.
+template <class C, int OUT, bool EDGE, bool TR>
 __device__ __forceinline__ void store_block(const GemmArgs& g, int row, int col0, const typename Mfma<C::DT, C::MF>::Acc& blk) {
-    constexpr int Q = C::ACC / 4, QS = 4 * C::KG;    // column groups per lane, distance between them
-    const bool row_ok = !EDGE || row < g.M;
-    const uint32_t row_off = (uint32_t)row * (uint32_t)g.N;
-    if constexpr (!VEC) {
+    constexpr int Q = C::ACC / 4, QS = 4 * C::KG;    // register groups per lane, distance between their rows / columns
+    if constexpr (!TR) {
 #pragma unroll
         for (int r = 0; r < C::ACC; r++) {
-            const int col = col0 + (r / 4) * QS + r % 4;
-            if (row_ok && (!EDGE || col < g.N)) {
-                const size_t o = (size_t)(row_off + (uint32_t)col);
+            const int rr = row + (r / 4) * QS + r % 4;
+            if (!EDGE || (rr < g.M && col0 < g.N)) {
+                const size_t o = (size_t)((uint32_t)rr * (uint32_t)g.N + (uint32_t)col0);
                 if (OUT == SK_F32) static_cast<float*>(g.D)[o] = blk[r];
                 else if (OUT == SK_BF16) static_cast<u16*>(g.D)[o] = to_bf16_bits(blk[r]);
                 else static_cast<_Float16*>(g.D)[o] = (_Float16)blk[r];
             }
         }
-    } else if constexpr (OUT == SK_F32) {
+        return;
+    }
+    const bool row_ok = !EDGE || row < g.M;
+    const uint32_t row_off = (uint32_t)row * (uint32_t)g.N;
+    if constexpr (OUT == SK_F32) {
 #pragma unroll
         for (int q = 0; q < Q; q++) {
             const int col = col0 + q * QS;
@@ -589,10 +596,10 @@ __device__ __forceinline__ void store_block(const GemmArgs& g, int row, int col0
 
 // Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): add the parked partials of the
 // contributors in ascending workgroup order (= ascending k), convert and store.  OUT selects the
-// output type, EDGE adds the bounds checks, VEC the vector stores.  row0 / col0: the lane's row and
-// first column in the wave's first block.  The big tiles work one block at a time, which keeps
-// their register need flat.
-template <class C, int OUT, bool EDGE, bool VEC>
+// output type, EDGE adds the bounds checks, TR says that the blocks are transposed (see store_block).
+// row0 / col0: the lane's (first) row and (first) column in the wave's first block.  The big tiles
+// work one block at a time, which keeps their register need flat.
+template <class C, int OUT, bool EDGE, bool TR>
 __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
                                                  const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
@@ -650,14 +657,16 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
                     src += C::BM * C::BN;
                 }
             }
-            store_block<C, OUT, EDGE, VEC>(g, row0 + mi * C::MF, col0 + ni * C::MF, blk);
+            store_block<C, OUT, EDGE, TR>(g, row0 + mi * C::MF, col0 + ni * C::MF, blk);
             __builtin_amdgcn_sched_barrier(0);
         }
 }
 
 // Atomic fix-up (Algorithm 1, lines 14-18): a segment that covers only part of the tile's
 // K-iterations adds its accumulators into the zero-initialised fp32 image with atomic adds; a
-// segment that covers the whole tile stores them.  row0 / col0 as in reduce_and_store.
+// segment that covers the whole tile stores them.  Blocks are not transposed here: the lanes of
+// one atomic instruction then sit side by side in a row of the image (two cache lines per
+// instruction instead of 32).
 template <class C, bool EDGE>
 __device__ __forceinline__ void add_to_image(const GemmArgs& g, int row0, int col0, bool partial,
                                              const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
@@ -665,10 +674,10 @@ __device__ __forceinline__ void add_to_image(const GemmArgs& g, int row0, int co
     for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
         for (int ni = 0; ni < C::NI; ni++) {
-            const int row = row0 + mi * C::MF;
+            const int col = col0 + ni * C::MF;
 #pragma unroll
             for (int r = 0; r < C::ACC; r++) {
-                const int col = col0 + ni * C::MF + (r / 4) * (4 * C::KG) + r % 4;
+                const int row = row0 + mi * C::MF + (r / 4) * (4 * C::KG) + r % 4;
                 if (!EDGE || (row < g.M && col < g.N)) {
                     float* p = g.image + (size_t)((uint32_t)row * (uint32_t)g.N + (uint32_t)col);
                     if (partial) unsafeAtomicAdd(p, acc[mi][ni][r]);
@@ -686,6 +695,9 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / C::WN, wn = wave % C::WN;
     const int x = logical_wg(blockIdx.x, g.grid);
+    // transposed accumulator blocks (vector stores) where D's rows are 16-byte aligned; the atomic
+    // fix-up and the element-wise stores of unaligned problems want the lanes side by side in a row
+    constexpr bool TR = ALIGNED && !ATOMIC;
     FragMap<C> fm;
     fm.init();
 
@@ -729,10 +741,10 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
             for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
-        mac_loop<C, ALIGNED>(g, m0, n0, k_begin, k_end, smem, fm, acc);
+        mac_loop<C, ALIGNED, TR>(g, m0, n0, k_begin, k_end, smem, fm, acc);
 
         if (ATOMIC) {
-            int row0 = m0 + wm * C::WTM + lane % C::MF, col0 = n0 + wn * C::WTN + 4 * (lane / C::MF);
+            int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
             asm volatile("" : "+v"(row0), "+v"(col0));
             const bool partial = k_begin > 0 || k_end < g.ipt;
             if (m0 + C::BM > g.M || n0 + C::BN > g.N) add_to_image<C, true>(g, row0, col0, partial, acc);
@@ -802,20 +814,21 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         }
 
         // ---- epilogue: fp32 accumulators -> D
-        int row0 = m0 + wm * C::WTM + lane % C::MF, col0 = n0 + wn * C::WTN + 4 * (lane / C::MF);
+        int row0 = m0 + wm * C::WTM + (TR ? lane % C::MF : 4 * (lane / C::MF));
+        int col0 = n0 + wn * C::WTN + (TR ? 4 * (lane / C::MF) : lane % C::MF);
         asm volatile("" : "+v"(row0), "+v"(col0));
         const float* part0 = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
         asm volatile("" : "+v"(part0));
         const bool edge = m0 + C::BM > g.M || n0 + C::BN > g.N;
         if (g.out_dtype == SK_BF16) {
-            if (edge) reduce_and_store<C, SK_BF16, true, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_BF16, false, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_BF16, true, TR>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_BF16, false, TR>(g, row0, col0, part0, n_contrib, acc);
         } else if (g.out_dtype == SK_F16) {
-            if (edge) reduce_and_store<C, SK_F16, true, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F16, false, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_F16, true, TR>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_F16, false, TR>(g, row0, col0, part0, n_contrib, acc);
         } else {
-            if (edge) reduce_and_store<C, SK_F32, true, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F32, false, ALIGNED>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_F32, true, TR>(g, row0, col0, part0, n_contrib, acc);
+            else reduce_and_store<C, SK_F32, false, TR>(g, row0, col0, part0, n_contrib, acc);
         }
     }
 }

@@ -33,7 +33,7 @@ def time_policy(sk, torch, plan, dA, dB, dD, stream, est_ms):
     return e0.elapsed_time(e1) / reps, reps
 
 
-def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0):
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None):
     import torch
     import paper_2408_11417_amd as sk
 
@@ -67,7 +67,7 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0):
     for idx, (M, N, K) in enumerate(shapes):
         plans, infos = [], []
         for p in range(sk.SK_NUM_POLICIES):
-            plan = sk.sk_plan(M, N, K, p, None, 256, dtype_code, dtype_code)
+            plan = sk.sk_plan(M, N, K, p, tile, 256, dtype_code, dtype_code)
             sk.sk_plan_set_fixup(plan, fixup)
             assert sk.sk_workspace_bytes(plan) <= ws_bytes
             sk.sk_plan_set_workspace(plan, ws_ptr, ws_bytes)
@@ -119,6 +119,7 @@ def main():
     ap.add_argument("--seed", type=int, default=4)
     ap.add_argument("--out", default="sweep_bf16.json")
     ap.add_argument("--first", type=int, default=0, help="only the first N shapes (smoke runs)")
+    ap.add_argument("--tile", default="", help="blk_m,blk_n,blk_k for every shape instead of the library's own choice")
     ap.add_argument("--fixup", choices=("flags", "atomic"), default="flags",
                     help="how split tiles are combined (atomic = Algorithm 1, lines 14-18)")
     args = ap.parse_args()
@@ -126,7 +127,8 @@ def main():
     shapes = inputs.sweep_shapes(args.shapes, args.seed)
     if args.first:
         shapes = shapes[:args.first]
-    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0)
+    tile = tuple(int(v) for v in args.tile.split(",")) if args.tile else None
+    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0, tile=tile)
     return 0
 
 
