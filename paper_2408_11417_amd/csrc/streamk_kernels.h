@@ -195,6 +195,11 @@ __device__ __forceinline__ int logical_wg(int hw, int grid) {
     return (grid % 8 == 0) ? (hw % 8) * (grid / 8) + hw / 8 : hw;
 }
 
+// 16 bytes whose address is only known to be a multiple of the element size (rows of a matrix whose
+// leading dimension is not a multiple of 8 elements start anywhere); the compiler picks the access.
+struct __attribute__((packed, aligned(1))) Piece1 { u32x4 v; };
+struct __attribute__((packed, aligned(2))) Piece2 { u32x4 v; };
+
 template <int ES, bool ALIGNED>
 __device__ __forceinline__ uint4 load_piece(const unsigned char* __restrict__ base, int row, int col, int rows, int cols) {
     // 16 bytes = 16 / ES consecutive elements of a row-major matrix with `cols` columns, zero beyond its edges
@@ -203,7 +208,10 @@ __device__ __forceinline__ uint4 load_piece(const unsigned char* __restrict__ ba
         const unsigned char* p = base + (size_t)((uint32_t)row * (uint32_t)cols + (uint32_t)col) * ES;
         if (ALIGNED) {
             if (col < cols) v = *reinterpret_cast<const uint4*>(p);
-        } else {
+        } else if (col + 16 / ES <= cols) {          // the whole piece lies inside the row
+            const u32x4 w = ES == 2 ? reinterpret_cast<const Piece2*>(p)->v : reinterpret_cast<const Piece1*>(p)->v;
+            v = make_uint4(w[0], w[1], w[2], w[3]);
+        } else if (col < cols) {                     // the piece that straddles the end of the row
             unsigned char e[16];
 #pragma unroll
             for (int i = 0; i < 16; i++) e[i] = (col + i / ES < cols) ? p[i] : (unsigned char)0;
