@@ -257,3 +257,14 @@ def test_hip_graph_replay_matches_eager(fixup):
         assert r.check() == sk.SK_OK
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("index", list(range(7, 500, 45)))
+def test_sweep_shapes_sampled_rows(index):
+    # sizes of the 500-shape tuning sweep, under the library's own tile choice as the sweep runs them
+    M, N, K = inputs.sweep_shapes(500, 4)[index]
+    A, B = inputs.uniform_pair(M, N, K, inputs.BF16, 100 + index)
+    rows = inputs.sample_rows(M, 6, index)
+    ref = G.gemm_fp64(A, B, G.BF16, rows=rows)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(A, B, inputs.BF16, policy, None, rows=rows, ref=ref)

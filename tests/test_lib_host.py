@@ -109,6 +109,21 @@ def test_gemm_rejects_bad_arguments_without_touching_the_gpu():
     sk.sk_plan_destroy(p)
 
 
+def test_gemm_rejects_sizes_beyond_the_kernels_index_range():
+    # the kernels index A and B with 32-bit byte offsets and D with 32-bit element offsets; larger
+    # problems are refused up front (planning them is still allowed)
+    for M, N, K in ((1 << 16, 64, 1 << 15), (64, 1 << 16, 1 << 15), (1 << 16, 1 << 16, 64)):
+        p = sk.sk_plan(M, N, K, sk.SK_POLICY_DP)
+        assert sk.sk_plan_info(p)["tiles"] >= 1
+        assert sk.sk_gemm_status(256, 512, 768, p) == sk.SK_ERR_UNSUPPORTED
+        sk.sk_plan_destroy(p)
+    # just inside the range: gets as far as the workspace check (the plan splits tiles), nothing is launched
+    p = sk.sk_plan((1 << 16) - 16, 64, (1 << 14) + 64, sk.SK_POLICY_ALL_SK, (256, 128, 64), 250)
+    assert any(seg[4] != sk.SK_ROLE_FULL for seg in sk.sk_plan_segments(p))
+    assert sk.sk_gemm_status(256, 512, 768, p) == sk.SK_ERR_WORKSPACE
+    sk.sk_plan_destroy(p)
+
+
 def test_fixup_mode_setter_and_workspace_need():
     import ctypes
     lib = sk.binding._lib
