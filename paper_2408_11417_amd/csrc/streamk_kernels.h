@@ -134,6 +134,8 @@ struct Cfg {
     // k-step's operands, then multiply the current ones".
     static constexpr int FRAG_REGS = (MI + NI) * (FP8 ? 8 : 4), ACC_REGS = MI * NI * ACC;
     static constexpr bool PIN_ORDER = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 64 <= 256 : 2 * FRAG_REGS + 64 <= 160;
+    // register-staged path: room to hold the next stage's pieces (4 registers each) during the matrix-core work
+    static constexpr bool STAGE_AHEAD = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 4 * (CA + CB) + 64 <= 256 : 2 * FRAG_REGS + 4 * (CA + CB) + 64 <= 224;
     static_assert(WTM % MF == 0 && WTN % MF == 0 && BK % KM == 0, "tile does not divide");
     static_assert(CPA == 4 || CPA == 8 || CPA == 16, "A swizzle assumes 64/128/256-byte rows");
     static_assert(CPB >= 16, "B swizzle assumes rows of at least 256 bytes");
@@ -224,39 +226,44 @@ __device__ __forceinline__ uint4 load_piece(const unsigned char* __restrict__ ba
     return v;
 }
 
-// Register-staged fill of one stage with zero fill at every edge (same LDS image as the DMA path).
-template <class C, bool ALIGNED>
-__device__ __forceinline__ void fill_stage_staged(const GemmArgs& g, int m0, int n0, int kit, unsigned char* a_stage, unsigned char* b_stage) {
-    const int tid = threadIdx.x;
-    const unsigned char* A = static_cast<const unsigned char*>(g.A);
-    const unsigned char* B = static_cast<const unsigned char*>(g.B);
-    const int k0 = kit * C::BK;
+// Register-staged fill of one stage with zero fill at every edge (same LDS image as the DMA path),
+// in two halves: fetch the stage's pieces into registers, and later park them in LDS.
+template <class C, bool ALIGNED> struct StagedFill {
     uint4 ra[C::CA], rb[C::CB];
+    __device__ __forceinline__ void fetch(const GemmArgs& g, int m0, int n0, int kit) {
+        const int tid = threadIdx.x;
+        const unsigned char* A = static_cast<const unsigned char*>(g.A);
+        const unsigned char* B = static_cast<const unsigned char*>(g.B);
+        const int k0 = kit * C::BK;
 #pragma unroll
-    for (int i = 0; i < C::CA; i++) {
-        const int p = tid + i * C::THREADS;
-        if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES)
-            ra[i] = load_piece<C::ES, ALIGNED>(A, m0 + p / C::CPA, k0 + (p % C::CPA) * C::PE, g.M, g.K);
-    }
+        for (int i = 0; i < C::CA; i++) {
+            const int p = tid + i * C::THREADS;
+            if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES)
+                ra[i] = load_piece<C::ES, ALIGNED>(A, m0 + p / C::CPA, k0 + (p % C::CPA) * C::PE, g.M, g.K);
+        }
 #pragma unroll
-    for (int i = 0; i < C::CB; i++) {
-        const int p = tid + i * C::THREADS;
-        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES)
-            rb[i] = load_piece<C::ES, ALIGNED>(B, k0 + p / C::CPB, n0 + (p % C::CPB) * C::PE, g.K, g.N);
+        for (int i = 0; i < C::CB; i++) {
+            const int p = tid + i * C::THREADS;
+            if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES)
+                rb[i] = load_piece<C::ES, ALIGNED>(B, k0 + p / C::CPB, n0 + (p % C::CPB) * C::PE, g.K, g.N);
+        }
     }
-    uint4* sA = reinterpret_cast<uint4*>(a_stage);
-    uint4* sB = reinterpret_cast<uint4*>(b_stage);
+    __device__ __forceinline__ void park(unsigned char* a_stage, unsigned char* b_stage) const {
+        const int tid = threadIdx.x;
+        uint4* sA = reinterpret_cast<uint4*>(a_stage);
+        uint4* sB = reinterpret_cast<uint4*>(b_stage);
 #pragma unroll
-    for (int i = 0; i < C::CA; i++) {
-        const int p = tid + i * C::THREADS, r = p / C::CPA;
-        if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES) sA[r * C::CPA + ((p % C::CPA) ^ swz_a<C::CPA>(r))] = ra[i];
-    }
+        for (int i = 0; i < C::CA; i++) {
+            const int p = tid + i * C::THREADS, r = p / C::CPA;
+            if (C::A_PIECES % C::THREADS == 0 || p < C::A_PIECES) sA[r * C::CPA + ((p % C::CPA) ^ swz_a<C::CPA>(r))] = ra[i];
+        }
 #pragma unroll
-    for (int i = 0; i < C::CB; i++) {
-        const int p = tid + i * C::THREADS, k = p / C::CPB;
-        if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES) sB[k * C::CPB + ((p % C::CPB) ^ swz_b<C::FP8>(k))] = rb[i];
+        for (int i = 0; i < C::CB; i++) {
+            const int p = tid + i * C::THREADS, k = p / C::CPB;
+            if (C::B_PIECES % C::THREADS == 0 || p < C::B_PIECES) sB[k * C::CPB + ((p % C::CPB) ^ swz_b<C::FP8>(k))] = rb[i];
+        }
     }
-}
+};
 
 // Per-tile addressing of the LDS-DMA loads: lane l of this wave's j-th A instruction fills A
 // position (j * NW + wave) * 64 + l.  Rows beyond M and columns beyond N are clamped to the last
@@ -519,12 +526,18 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         }
         __syncthreads();                             // all reads done before the next segment refills
     } else {
+        // Register-staged path, two LDS slots.  Where registers allow (STAGE_AHEAD) the pieces of
+        // stage k+1 are requested before the matrix-core work of stage k and parked after it.
+        StagedFill<C, ALIGNED> sf;
+        if (C::STAGE_AHEAD) sf.fetch(g, m0, n0, k_begin);
         for (int k = k_begin; k < k_end; k++) {
             const int slot = (k - k_begin) & 1;
             unsigned char* a_stage = smem + slot * C::A_BYTES;
             unsigned char* b_stage = smem + C::B_RING + slot * C::B_BYTES;
-            fill_stage_staged<C, ALIGNED>(g, m0, n0, k, a_stage, b_stage);
-            __syncthreads();
+            if (!C::STAGE_AHEAD) sf.fetch(g, m0, n0, k);
+            sf.park(a_stage, b_stage);
+            __syncthreads();      // also: every wave is done with the other slot (stage k-1)
+            if (C::STAGE_AHEAD && k + 1 < k_end) sf.fetch(g, m0, n0, k + 1);
             mac_stage<C, TR>(a_stage, b_stage, fm, acc);
         }
         __syncthreads();
