@@ -54,7 +54,9 @@ def test_no_false_negatives_and_selection_rules():
         ps, _, _ = sel.select(r)
         assert (mask >> ps) & 1
     sel.close()
-    assert selector.fallback_policy(512) == sk.SK_POLICY_DP and selector.fallback_policy(495) == sk.SK_POLICY_SK1_DP
+    assert selector.fallback_policy(512) == sk.SK_POLICY_DP and selector.fallback_policy(495) == sk.SK_POLICY_DP
+    assert selector.fallback_policy(290) == sk.SK_POLICY_SK1_DP and selector.fallback_policy(100) == sk.SK_POLICY_SK1_DP
+    assert selector.fallback_policy(154) == sk.SK_POLICY_DP and selector.fallback_policy(153) == sk.SK_POLICY_SK1_DP
 
 
 def test_exact_filters_equal_oracle_filters_and_batch_query():
