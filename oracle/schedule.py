@@ -63,7 +63,7 @@ def cdiv(a, b):
 
 
 def decompose(M, N, K, blk_m, blk_n, blk_k):
-    """Algorithm 1, lines 2-3: tile grid, iterations per tile, total iterations."""
+    """Algorithm 1, problem decomposition: tile grid, iterations per tile, total iterations."""
     tiles_m = cdiv(M, blk_m)
     tiles_n = cdiv(N, blk_n)
     iters_per_tile = cdiv(K, blk_k)
@@ -107,14 +107,14 @@ def tile_coords(tile, tiles_m, tiles_n, order=ORDER_ROW_MAJOR):
 
 
 def wg_sk_range(x, sk_iters, iters_per_wg):
-    """Algorithm 1, lines 5-6, clamped to the Stream-K iteration total (reading R4)."""
+    """Algorithm 1, a workgroup's iteration range, clamped to the Stream-K iteration total (reading R4)."""
     begin = min(x * iters_per_wg, sk_iters)
     end = min((x + 1) * iters_per_wg, sk_iters)
     return begin, end
 
 
 def wg_sk_segments(x, begin, end, iters_per_tile):
-    """Algorithm 1, lines 7-20: cut [begin, end) at tile boundaries."""
+    """Algorithm 1, the outer loop over a workgroup's range: cut [begin, end) at tile boundaries."""
     segs = []
     it = begin
     while it < end:
@@ -149,7 +149,7 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR):
     sk_tiles = sk_tile_count(tiles, g, policy)
     dp_tiles = tiles - sk_tiles
     sk_iters = sk_tiles * ipt
-    ipw = cdiv(sk_iters, g)                       # Algorithm 1, line 4, on the SK region
+    ipw = cdiv(sk_iters, g)                       # Algorithm 1, iterations per workgroup, on the SK region
     ranges, segments = [], []
     for x in range(g):
         begin, end = wg_sk_range(x, sk_iters, ipw)

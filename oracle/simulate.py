@@ -3,9 +3,9 @@
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
 It proves, without a GPU, that a schedule from oracle/schedule.py together with
-the workspace-and-flags fix-up (Sec. 5.3's alternative to the atomic adds of
-Algorithm 1, lines 14-18) computes the GEMM: every segment runs Algorithm 1's
-MAC_loop (line 13) over its k-iterations into an fp32 accumulator tile; a
+the workspace-and-flags fix-up (Sec. 5.3's alternative to the atomic adds at the
+end of Algorithm 1's loop body) computes the GEMM: every segment runs Algorithm 1's
+MAC_loop over its k-iterations into an fp32 accumulator tile; a
 CONTRIB segment parks its tile in the workspace slot of its workgroup; an OWNER
 adds the parked tiles of its contributors in ascending workgroup order and
 stores; a FULL segment stores directly.  Contributors always execute before the
