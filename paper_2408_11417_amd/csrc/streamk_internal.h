@@ -16,6 +16,7 @@ struct sk_plan_t {
 // Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]
 constexpr size_t SK_FLAG_STRIDE = 128;
 constexpr int SK_GROUP_ROWS = 8;   // tile rows per band of the grouped tile order
+constexpr int SK_TREE_GROUP = 8;   // contributors per group in the two-level reduction of tiles shared by many workgroups
 inline size_t sk_ws_status_offset(int grid) { return (size_t)grid * SK_FLAG_STRIDE; }
 inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_FLAG_STRIDE + 384; }
 

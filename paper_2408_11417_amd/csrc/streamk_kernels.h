@@ -544,6 +544,63 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
     }
 }
 
+// Wait until `count` contributors have raised their flags: workgroups first, first + stride, ...
+// The lanes of the calling wave watch up to 64 flags at a time, one flag each, so the wait costs one
+// round trip however many flags there are.  A lane that has seen its flag takes it down again:
+// every flag is watched by exactly one lane of one waiting workgroup, so all flags are back at zero
+// when the kernel ends and the next launch (or a replay of a captured launch) starts from the same
+// state.  The wait is bounded: after spin_limit unsuccessful polls it is recorded in the status word
+// and given up.
+__device__ __forceinline__ void wait_flags(const GemmArgs& g, int first, int count, int stride) {
+    const int lane = threadIdx.x % 64;
+    uint32_t polls = 0;
+    for (int base = 0; base < count; base += 64) {
+        const bool mine = base + lane < count;
+        uint32_t* flag = g.flags + (size_t)(first + (mine ? base + lane : 0) * stride) * (SK_FLAG_STRIDE / 4);
+        bool seen = !mine;
+        while (true) {
+            if (!seen && __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                seen = true;
+                __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (__all(seen)) break;
+            if (polls++ >= g.spin_limit) {
+                if (lane == 0) __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+}
+
+// sum += the parked partial tiles src, src + stride, ... (`count` of them, this lane's share), in
+// that order.  For tiles with at most 64 accumulators per lane: a contributor's whole share is
+// fetched at once and G contributors per round trip (about 64 registers of loads in flight).
+template <class C>
+__device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&sum)[C::MI][C::NI], const float* src, int count, size_t stride) {
+    constexpr int G = 64 / C::ACC_REGS < 8 ? 64 / C::ACC_REGS : 8;
+    auto add_group = [&](const float* p, auto cnt) {
+        constexpr int CNT = decltype(cnt)::value;
+        float v[CNT][C::ACC_REGS];
+#pragma unroll
+        for (int j = 0; j < CNT; j++)
+#pragma unroll
+            for (int i = 0; i < C::ACC_REGS; i++)
+                v[j][i] = __hip_atomic_load(p + j * stride + i * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < CNT; j++)
+#pragma unroll
+            for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+                for (int ni = 0; ni < C::NI; ni++)
+#pragma unroll
+                    for (int r = 0; r < C::ACC; r++) sum[mi][ni][r] += v[j][(mi * C::NI + ni) * C::ACC + r];
+    };
+    int c = 0;
+    for (; c + G <= count; c += G, src += G * stride) add_group(src, std::integral_constant<int, G>());
+    for (; c < count; c++, src += stride) add_group(src, std::integral_constant<int, 1>());
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return (uint32_t)to_bf16_bits(lo) | ((uint32_t)to_bf16_bits(hi) << 16); }
 __device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
     return (uint32_t)__builtin_bit_cast(u16, (_Float16)lo) | ((uint32_t)__builtin_bit_cast(u16, (_Float16)hi) << 16);
@@ -616,13 +673,13 @@ __device__ __forceinline__ void store_block(const GemmArgs& g, int row, int col0
 }
 
 // Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): add the parked partials of the
-// contributors in ascending workgroup order (= ascending k), convert and store.  OUT selects the
+// contributors part0, part0 + part_stride, ... (ascending workgroup order = ascending k), convert and store.  OUT selects the
 // output type, EDGE adds the bounds checks, TR says that the blocks are transposed (see store_block).
 // row0 / col0: the lane's (first) row and (first) column in the wave's first block.  The big tiles
 // work one block at a time, which keeps their register need flat.
 template <class C, int OUT, bool EDGE, bool TR>
 __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
-                                                 const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+                                                 size_t part_stride, const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
     // Tiles with few accumulators per lane fetch a contributor's whole share at once (one round trip
     // per contributor instead of one per block and contributor); the big tiles have no registers for that.
@@ -633,30 +690,7 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
             for (int ni = 0; ni < C::NI; ni++) sum[mi][ni] = acc[mi][ni];
-        // G contributors per round trip (about 64 registers of loads in flight); the additions keep
-        // the ascending contributor order
-        constexpr int G = 64 / C::ACC_REGS < 8 ? 64 / C::ACC_REGS : 8;
-        auto add_group = [&](const float* src, auto count) {
-            constexpr int CNT = decltype(count)::value;
-            float v[CNT][C::ACC_REGS];
-#pragma unroll
-            for (int j = 0; j < CNT; j++)
-#pragma unroll
-                for (int i = 0; i < C::ACC_REGS; i++)
-                    v[j][i] = __hip_atomic_load(src + (size_t)j * (C::BM * C::BN) + i * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int j = 0; j < CNT; j++)
-#pragma unroll
-                for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-                    for (int ni = 0; ni < C::NI; ni++)
-#pragma unroll
-                        for (int r = 0; r < C::ACC; r++) sum[mi][ni][r] += v[j][(mi * C::NI + ni) * C::ACC + r];
-        };
-        const float* src = part0;
-        int c = 0;
-        for (; c + G <= n_contrib; c += G, src += (size_t)G * (C::BM * C::BN)) add_group(src, std::integral_constant<int, G>());
-        for (; c < n_contrib; c++, src += C::BM * C::BN) add_group(src, std::integral_constant<int, 1>());
+        add_partials<C>(sum, part0, n_contrib, part_stride);
     }
 #pragma unroll
     for (int mi = 0; mi < C::MI; mi++)
@@ -675,7 +709,7 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
                         v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                     for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
-                    src += C::BM * C::BN;
+                    src += part_stride;
                 }
             }
             store_block<C, OUT, EDGE, TR>(g, row0 + mi * C::MF, col0 + ni * C::MF, blk);
@@ -774,13 +808,36 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         }
 
         // ---- fix-up
-        // (the empty asm statements keep the per-block addresses from being computed once, ahead
-        // of the persistent loop, where they would occupy registers for the whole kernel)
+        // Tiles shared by many workgroups are reduced in two levels (TREE; small tiles only, the
+        // big ones never have that many contributors): every SK_TREE_GROUP-th contributor first
+        // adds the partials of the contributors behind it to its own accumulators, so the owner
+        // collects one partial per group.  The order of the additions stays fixed.
+        constexpr bool TREE = C::ACC_REGS <= 64;
+        int tile_first_wg = 0, n_all = 0;                               // the tile's owner, its number of contributors
+        if (k_begin > 0 || k_end < g.ipt) {                             // (only split tiles; ipw is 0 in a plan without Stream-K work)
+            tile_first_wg = (int)((uint32_t)(tile * g.ipt) / (uint32_t)g.ipw);
+            n_all = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw) - tile_first_wg;
+        }
+        const bool two_level = TREE && n_all >= 2 * SK_TREE_GROUP;
         if (k_begin > 0) {
-            // contributor: park the accumulators (register order, coalesced), then signal
+            // contributor
+            if constexpr (TREE) {
+                const int j = x - tile_first_wg;                        // 1 .. n_all
+                if (two_level && (j - 1) % SK_TREE_GROUP == 0) {        // group leader: members j+1 .. j+GROUP-1
+                    const int members = (j + SK_TREE_GROUP - 1 <= n_all ? j + SK_TREE_GROUP - 1 : n_all) - j;
+                    if (wave == 0) wait_flags(g, x + 1, members, 1);
+                    __syncthreads();
+                    const float* mp = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
+                    asm volatile("" : "+v"(mp));
+                    add_partials<C>(acc, mp, members, (size_t)(C::BM * C::BN));
+                }
+            }
+            // park the accumulators (register order, coalesced), then signal.
             // Partial tiles are stored and loaded with device-scope atomic accesses (one dword
             // per lane, lanes contiguous): these are coherent across the XCDs' L2 caches by
             // themselves, so no L2 write-back / invalidate is needed around the exchange.
+            // (the empty asm statements keep the per-block addresses from being computed once, ahead
+            // of the persistent loop, where they would occupy registers for the whole kernel)
             float* slot = g.partials + (size_t)x * (C::BM * C::BN) + tid;
             asm volatile("" : "+v"(slot));
 #pragma unroll
@@ -800,38 +857,17 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             continue;
         }
         int n_contrib = 0;
+        size_t part_stride = (size_t)(C::BM * C::BN);
         if (k_end < g.ipt) {
-            // owner: contributors are the following workgroups up to the one holding the tile's
-            // last iteration.  Wait for all of them; the epilogue adds their partials in a fixed
-            // order, so the result does not depend on timing.
-            const int last = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
-            if (wave == 0) {
-                // the lanes of the first wave watch up to 64 flags at a time, one flag each, so the
-                // wait costs one round trip however many contributors there are.  A lane that has
-                // seen its flag takes it down again: every flag is watched by exactly one lane of
-                // one owner, so all flags are back at zero when the kernel ends and the next
-                // launch (or a replay of a captured launch) starts from the same state.
-                uint32_t polls = 0;
-                for (int base = x + 1; base <= last; base += 64) {
-                    const bool mine = base + lane <= last;
-                    uint32_t* flag = g.flags + (size_t)(mine ? base + lane : last) * (SK_FLAG_STRIDE / 4);
-                    bool seen = !mine;
-                    while (true) {
-                        if (!seen && __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
-                            seen = true;
-                            __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        }
-                        if (__all(seen)) break;
-                        if (polls++ >= g.spin_limit) {   // bounded wait: record and go on
-                            if (lane == 0) __hip_atomic_store(g.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(2);
-                    }
-                }
-            }
+            // owner (x == tile_first_wg): contributors are the following workgroups up to the one
+            // holding the tile's last iteration - or, with two levels, their group leaders.  Wait for
+            // all of them; the epilogue adds their partials in a fixed order, so the result does
+            // not depend on timing.
+            const int step = two_level ? SK_TREE_GROUP : 1;
+            n_contrib = (n_all + step - 1) / step;
+            part_stride *= step;
+            if (wave == 0) wait_flags(g, x + 1, n_contrib, step);
             __syncthreads();
-            n_contrib = last - x;
         }
 
         // ---- epilogue: fp32 accumulators -> D
@@ -842,14 +878,14 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         asm volatile("" : "+v"(part0));
         const bool edge = m0 + C::BM > g.M || n0 + C::BN > g.N;
         if (g.out_dtype == SK_BF16) {
-            if (edge) reduce_and_store<C, SK_BF16, true, TR>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_BF16, false, TR>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_BF16, true, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
+            else reduce_and_store<C, SK_BF16, false, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
         } else if (g.out_dtype == SK_F16) {
-            if (edge) reduce_and_store<C, SK_F16, true, TR>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F16, false, TR>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_F16, true, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
+            else reduce_and_store<C, SK_F16, false, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
         } else {
-            if (edge) reduce_and_store<C, SK_F32, true, TR>(g, row0, col0, part0, n_contrib, acc);
-            else reduce_and_store<C, SK_F32, false, TR>(g, row0, col0, part0, n_contrib, acc);
+            if (edge) reduce_and_store<C, SK_F32, true, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
+            else reduce_and_store<C, SK_F32, false, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
         }
     }
 }

@@ -268,3 +268,28 @@ def test_sweep_shapes_sampled_rows(index):
     ref = G.gemm_fp64(A, B, G.BF16, rows=rows)
     for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
         _run_and_compare(A, B, inputs.BF16, policy, None, rows=rows, ref=ref)
+
+
+@pytest.mark.parametrize("blk,shape", [((32, 128, 64), (64, 208, 7872)), ((16, 128, 64), (48, 256, 6208)),
+                                       ((64, 128, 64), (128, 128, 16448)), ((128, 128, 64), (128, 256, 8256)),
+                                       ((32, 128, 64), (32, 1024, 4160)), (None, (112, 128, 3552))])
+def test_tiles_shared_by_many_workgroups(blk, shape):
+    # few tiles, long K: 16 ... 120 contributors per tile, reduced in two levels (groups of 8 behind a leader)
+    M, N, K = shape
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 41)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for policy in (sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(A, B, inputs.BF16, policy, blk, grid=256, out_dtype=sk.SK_F32, ref=ref, exact=True, launches=3)
+    A, B = inputs.uniform_pair(M, N, K, inputs.BF16, 42)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_ALL_SK, blk, grid=256, ref=ref)
+    # the order of the additions is fixed: bit-identical from run to run
+    dA, dB = to_device(A), to_device(B)
+    r = Runner(M, N, K, sk.SK_POLICY_ALL_SK, blk, 256, inputs.BF16, sk.SK_F32)
+    try:
+        first = r.run(dA, dB).clone()
+        for _ in range(5):
+            assert torch.equal(r.run(dA, dB), first)
+        assert r.check() == sk.SK_OK
+    finally:
+        r.close()
