@@ -196,9 +196,18 @@ int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls);
  * into a HIP graph may be replayed (make one ordinary launch of the plan first:
  * the first use of a kernel sets its LDS limit and asks for its occupancy, which
  * capture does not allow).
- * Errors: INVALID_ARG, UNSUPPORTED (no kernel for tile + dtype, or the grid
- * cannot be co-resident while the plan has split tiles), WORKSPACE (plan has
- * split tiles but no workspace), HIP (launch failed). */
+ * Co-residency: under SK_FIXUP_FLAGS a tile owner waits inside the kernel for
+ * workgroups of the same launch, so all `grid` workgroups must be on the device
+ * at once.  sk_gemm checks that against an otherwise idle device; the caller
+ * must not let such a launch overlap with other kernels that occupy compute
+ * units (e.g. a second sk_gemm on another stream): two launches that each hold
+ * part of the device can wait for each other until the bounded wait gives up
+ * (SK_ERR_TIMEOUT from sk_plan_check, D invalid).  Plans without split tiles and
+ * SK_FIXUP_ATOMIC launches never wait and may overlap freely.
+ * Errors: INVALID_ARG, UNSUPPORTED (no kernel for tile + dtype + fix-up mode,
+ * sizes beyond the kernels' 32-bit index range: M*K or K*N >= 2^31 elements,
+ * M*N >= 2^32, or the grid cannot be co-resident while the plan has split
+ * tiles), WORKSPACE (plan has split tiles but no workspace), HIP (launch failed). */
 int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream);
 
 /* Blocking: waits for `stream` and reads the workspace status word.  Returns
