@@ -77,6 +77,14 @@ typedef enum {
  * additions depends on timing, so D may differ in the last bits between runs. */
 typedef enum { SK_FIXUP_FLAGS = 0, SK_FIXUP_ATOMIC = 1 } sk_fixup;
 
+/* Which phase a workgroup runs first.  STREAMK_FIRST (default): its Stream-K
+ * iterations, then its data-parallel tiles, so that the exchange of partial
+ * tiles overlaps with data-parallel work (Sec. 3.2, Sec. 4.1).
+ * DATA_PARALLEL_FIRST: the earlier hybrid that Sec. 3.2 describes - data-parallel
+ * batches followed by the Stream-K work; kept for comparison.  Which tiles are
+ * split and which workgroup gets which work is the same under both. */
+typedef enum { SK_STREAMK_FIRST = 0, SK_DATA_PARALLEL_FIRST = 1 } sk_batch_order;
+
 /* How a tile index maps to a position in the tile grid.  The schedule (which
  * workgroup runs which tile index) does not depend on it.  GROUPED follows the
  * remark of Sec. 5.3 that work should be handed out with cache locality in
@@ -147,8 +155,8 @@ int sk_plan_info(const sk_plan_t* plan, sk_plan_header* out);
 int sk_plan_ranges(const sk_plan_t* plan, sk_wg_range* out);
 
 /* Canonical expansion of the schedule: segments ordered by workgroup and, inside
- * a workgroup, in execution order (Stream-K segments, then data-parallel tiles;
- * Sec. 4.1).  out is host memory for `cap` entries (may be NULL when cap = 0);
+ * a workgroup, in execution order (Stream-K segments, then data-parallel tiles,
+ * Sec. 4.1; the other way round under SK_DATA_PARALLEL_FIRST).  out is host memory for `cap` entries (may be NULL when cap = 0);
  * *n receives the number of segments; INVALID_ARG if cap is too small (then *n
  * still receives the needed count). */
 int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t cap, size_t* n);
@@ -162,6 +170,11 @@ int sk_plan_tile_coords(const sk_plan_t* plan, int32_t tile, int32_t* tile_m, in
  * sk_plan_set_workspace: the workspace need depends on it.
  * Errors: INVALID_ARG (unknown mode, or a workspace is already attached). */
 int sk_plan_set_fixup(sk_plan_t* plan, int fixup);
+
+/* Choose the order of the two phases inside a workgroup (sk_batch_order;
+ * Sec. 3.2).  Changes the execution order that sk_plan_segments reports.
+ * Errors: INVALID_ARG (unknown value). */
+int sk_plan_set_batch_order(sk_plan_t* plan, int batch_order);
 
 /* Device bytes sk_gemm needs for this plan.  FLAGS: one flag line per workgroup,
  * a status word, and one fp32 partial tile (blk_m * blk_n) per workgroup.

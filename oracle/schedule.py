@@ -134,12 +134,15 @@ def wg_sk_segments(x, begin, end, iters_per_tile):
     return segs
 
 
-def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR):
+def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_first=False):
     """Full schedule for one problem: header, per-workgroup ranges, canonical segment list.
 
     The segment list is ordered by workgroup, and inside a workgroup in execution
     order: Stream-K segments ascending, then data-parallel tiles ascending
-    (Sec. 3.2 / 4.1: Stream-K batches come first).
+    (Sec. 3.2 / 4.1: Stream-K batches come first).  dp_first=True swaps the two
+    phases - the earlier hybrid that Sec. 3.2 describes, data-parallel batches
+    followed by the Stream-K work; which tiles are split and which workgroup gets
+    which work does not change.
     """
     if min(M, N, K, blk_m, blk_n, blk_k, g) < 1:
         raise ValueError("sizes must be positive")
@@ -153,17 +156,16 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR):
     ranges, segments = [], []
     for x in range(g):
         begin, end = wg_sk_range(x, sk_iters, ipw)
-        segs = wg_sk_segments(x, begin, end, ipt)
+        sk_segs = wg_sk_segments(x, begin, end, ipt)
         first = sk_tiles + x
         count = cdiv(tiles - first, g) if first < tiles else 0
-        for j in range(count):
-            segs.append(Segment(x, first + j * g, 0, ipt, ROLE_FULL))
+        dp_segs = [Segment(x, first + j * g, 0, ipt, ROLE_FULL) for j in range(count)]
         ranges.append(WgRange(begin, end, first if count else tiles, count))
-        segments.extend(segs)
+        segments.extend(dp_segs + sk_segs if dp_first else sk_segs + dp_segs)
     header = dict(M=M, N=N, K=K, policy=policy, blk_m=blk_m, blk_n=blk_n, blk_k=blk_k, grid=g,
                   tiles_m=tiles_m, tiles_n=tiles_n, tiles=tiles, iters_per_tile=ipt,
                   total_iters=total, sk_tiles=sk_tiles, dp_tiles=dp_tiles, sk_iters=sk_iters,
-                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g), tile_order=order)
+                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g), tile_order=order, dp_first=bool(dp_first))
     return Plan(header, ranges, segments)
 
 

@@ -30,9 +30,10 @@ SK_F16, SK_BF16, SK_FP8_E4M3, SK_F32 = 0, 1, 2, 3
 SK_ROLE_FULL, SK_ROLE_OWNER, SK_ROLE_CONTRIB = 0, 1, 2
 SK_ORDER_ROW_MAJOR, SK_ORDER_GROUPED = 0, 1
 SK_FIXUP_FLAGS, SK_FIXUP_ATOMIC = 0, 1
+SK_STREAMK_FIRST, SK_DATA_PARALLEL_FIRST = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
-           "sk_plan_set_fixup", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
+           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
            "sk_plan_destroy", "sk_default_tile", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
@@ -80,6 +81,7 @@ _lib.sk_workspace_bytes.restype = ctypes.c_size_t
 _lib.sk_plan_set_workspace.argtypes = [_vp, _vp, ctypes.c_size_t]
 _lib.sk_plan_set_spin_limit.argtypes = [_vp, ctypes.c_uint32]
 _lib.sk_plan_set_fixup.argtypes = [_vp, _int]
+_lib.sk_plan_set_batch_order.argtypes = [_vp, _int]
 _lib.sk_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sk_plan_check.argtypes = [_vp, _vp]
 _lib.sk_plan_destroy.argtypes = [_vp]
@@ -172,6 +174,10 @@ def sk_plan_set_workspace(plan, dev_ptr, nbytes):
 
 def sk_plan_set_fixup(plan, fixup):
     _check(_lib.sk_plan_set_fixup(plan, fixup), "sk_plan_set_fixup")
+
+
+def sk_plan_set_batch_order(plan, batch_order):
+    _check(_lib.sk_plan_set_batch_order(plan, batch_order), "sk_plan_set_batch_order")
 
 
 def sk_plan_set_spin_limit(plan, polls):

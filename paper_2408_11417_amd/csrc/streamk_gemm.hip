@@ -136,6 +136,7 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.sk_tiles = h.sk_tiles; g.ipw = h.iters_per_wg; g.grid = h.grid; g.sk_iters = (int)h.sk_iters;
     g.spin_limit = plan->spin_limit;
     g.out_dtype = h.out_dtype;
+    g.dp_first = plan->dp_first;
     if (atomic) {
         // Algorithm 1, lines 14-18 need C to start at zero: clear the image in-stream, accumulate, convert
         const size_t n = (size_t)h.M * (size_t)h.N;

@@ -11,6 +11,7 @@ struct sk_plan_t {
     uint32_t spin_limit = 1u << 24;
     int needs_fixup = 0;            // 1 if any tile is split over several workgroups
     int fixup = SK_FIXUP_FLAGS;     // how split tiles are combined
+    int dp_first = 0;               // 1: data-parallel tiles before the Stream-K iterations
 };
 
 // Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]

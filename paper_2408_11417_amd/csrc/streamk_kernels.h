@@ -46,6 +46,7 @@ struct GemmArgs {
     int tiles_m, tiles_n, tiles, ipt, sk_tiles, ipw, grid, sk_iters, tile_order;
     uint32_t spin_limit;
     int out_dtype;
+    int dp_first;          // 1: a workgroup runs its data-parallel tiles before its Stream-K iterations
 };
 
 // ---- matrix-core wrappers ---------------------------------------------------------------------
@@ -764,14 +765,15 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
 
     while (true) {
         int tile, k_begin, k_end;
-        if (it < it_end) {                       // Algorithm 1, lines 8-12
+        const bool dp_now = dp_tile < g.tiles && (g.dp_first || it >= it_end);
+        if (!dp_now && it < it_end) {            // Algorithm 1, lines 8-12
             tile = (int)((uint32_t)it / (uint32_t)g.ipt);
             const int tile_first = tile * g.ipt;
             k_begin = it - tile_first;
             const int stop = it_end < tile_first + g.ipt ? it_end : tile_first + g.ipt;
             k_end = stop - tile_first;
             it = tile_first + g.ipt;
-        } else if (dp_tile < g.tiles) {
+        } else if (dp_now) {
             tile = dp_tile; k_begin = 0; k_end = g.ipt;
             dp_tile += g.grid;
         } else {

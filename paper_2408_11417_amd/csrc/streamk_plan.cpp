@@ -25,13 +25,14 @@ bool dtype_in_ok(int d) { return d == SK_F16 || d == SK_BF16 || d == SK_FP8_E4M3
 bool dtype_out_ok(int d) { return d == SK_F16 || d == SK_BF16 || d == SK_F32; }
 
 // Segments of workgroup x, appended in execution order.
-void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_wg_range* range) {
+void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_wg_range* range, bool dp_first = false) {
     const int64_t ipt = h.iters_per_tile;
     int64_t it = x * (int64_t)h.iters_per_wg;
     int64_t end = it + h.iters_per_wg;
     if (it > h.sk_iters) it = h.sk_iters;
     if (end > h.sk_iters) end = h.sk_iters;
     if (range) { range->sk_iter_begin = it; range->sk_iter_end = end; }
+    const size_t at = out ? out->size() : 0;     // where this workgroup's segments start
     // Algorithm 1, lines 7-20: one segment per tile the range touches
     while (it < end) {
         const int64_t tile = it / ipt;
@@ -46,10 +47,14 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
         if (out) out->push_back(s);
         it = tile_first + ipt;
     }
-    // data-parallel tiles follow the Stream-K work (Sec. 4.1)
+    // data-parallel tiles follow the Stream-K work (Sec. 4.1) - or precede it (Sec. 3.2's earlier hybrid)
     int32_t count = 0;
     for (int64_t t = (int64_t)h.sk_tiles + x; t < h.tiles; t += h.grid) {
-        if (out) out->push_back(sk_segment{x, (int32_t)t, 0, (int32_t)ipt, SK_ROLE_FULL});
+        if (out) {
+            const sk_segment s{x, (int32_t)t, 0, (int32_t)ipt, SK_ROLE_FULL};
+            if (dp_first) out->insert(out->begin() + (std::ptrdiff_t)(at + count), s);
+            else out->push_back(s);
+        }
         ++count;
     }
     if (range) {
@@ -183,7 +188,7 @@ extern "C" int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t c
     if (!plan || !n || (!out && cap)) return SK_ERR_INVALID_ARG;
     std::vector<sk_segment> segs;
     try {
-        for (int x = 0; x < plan->h.grid; x++) expand_wg(plan->h, x, &segs, nullptr);
+        for (int x = 0; x < plan->h.grid; x++) expand_wg(plan->h, x, &segs, nullptr, plan->dp_first != 0);
     } catch (const std::bad_alloc&) {
         return SK_ERR_NOMEM;
     }
@@ -237,6 +242,12 @@ extern "C" size_t sk_workspace_bytes(const sk_plan_t* plan) {
 extern "C" int sk_plan_set_fixup(sk_plan_t* plan, int fixup) {
     if (!plan || (fixup != SK_FIXUP_FLAGS && fixup != SK_FIXUP_ATOMIC) || plan->workspace) return SK_ERR_INVALID_ARG;
     plan->fixup = fixup;
+    return SK_OK;
+}
+
+extern "C" int sk_plan_set_batch_order(sk_plan_t* plan, int batch_order) {
+    if (!plan || (batch_order != SK_STREAMK_FIRST && batch_order != SK_DATA_PARALLEL_FIRST)) return SK_ERR_INVALID_ARG;
+    plan->dp_first = batch_order == SK_DATA_PARALLEL_FIRST;
     return SK_OK;
 }
 

@@ -33,7 +33,7 @@ def time_policy(sk, torch, plan, dA, dB, dD, stream, est_ms):
     return e0.elapsed_time(e1) / reps, reps
 
 
-def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None):
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False):
     import torch
     import paper_2408_11417_amd as sk
 
@@ -69,6 +69,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
         for p in range(sk.SK_NUM_POLICIES):
             plan = sk.sk_plan(M, N, K, p, tile, 256, dtype_code, dtype_code)
             sk.sk_plan_set_fixup(plan, fixup)
+            if dp_first:
+                sk.sk_plan_set_batch_order(plan, sk.SK_DATA_PARALLEL_FIRST)
             assert sk.sk_workspace_bytes(plan) <= ws_bytes
             sk.sk_plan_set_workspace(plan, ws_ptr, ws_bytes)
             plans.append(plan)
@@ -109,7 +111,7 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
         if out_path and (idx % 50 == 49 or idx == len(shapes) - 1):
             with open(out_path, "w") as f:
                 json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256,
-                           "fixup": "atomic" if fixup else "flags", "records": records}, f)
+                           "fixup": "atomic" if fixup else "flags", "dp_first": bool(dp_first), "records": records}, f)
     return records
 
 
@@ -120,6 +122,8 @@ def main():
     ap.add_argument("--out", default="sweep_bf16.json")
     ap.add_argument("--first", type=int, default=0, help="only the first N shapes (smoke runs)")
     ap.add_argument("--tile", default="", help="blk_m,blk_n,blk_k for every shape instead of the library's own choice")
+    ap.add_argument("--dp-first", action="store_true",
+                    help="data-parallel batches before the Stream-K work (the earlier hybrid of Sec. 3.2)")
     ap.add_argument("--fixup", choices=("flags", "atomic"), default="flags",
                     help="how split tiles are combined (atomic = Algorithm 1, lines 14-18)")
     args = ap.parse_args()
@@ -128,7 +132,7 @@ def main():
     if args.first:
         shapes = shapes[:args.first]
     tile = tuple(int(v) for v in args.tile.split(",")) if args.tile else None
-    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0, tile=tile)
+    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0, tile=tile, dp_first=args.dp_first)
     return 0
 
 

@@ -20,15 +20,16 @@ ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16, inputs.E4M3: G.E4M3}
 
 
 def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False,
-                     fixup=sk.SK_FIXUP_FLAGS, launches=1):
+                     fixup=sk.SK_FIXUP_FLAGS, launches=1, dp_first=False):
     M, K = A.shape
     N = B.shape[1]
     print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s fixup=%d" %
           (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype, fixup), flush=True)
-    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup)
+    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup, dp_first=dp_first)
     try:
         # the library's schedule for this very launch equals the oracle's
-        o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"], r.info["tile_order"])
+        o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"], r.info["tile_order"],
+                   dp_first=dp_first)
         assert sk.sk_plan_segments(r.plan) == [tuple(s) for s in o.segments]
         dA, dB = to_device(A), to_device(B)
         for _ in range(launches):
@@ -293,3 +294,15 @@ def test_tiles_shared_by_many_workgroups(blk, shape):
         assert r.check() == sk.SK_OK
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("blk", [(128, 128, 64), (256, 128, 64), (256, 256, 64), (32, 128, 64)])
+def test_data_parallel_batches_first(blk):
+    # Sec. 3.2's earlier hybrid: the same work, data-parallel tiles before the Stream-K iterations, under both fix-ups
+    M, N, K = 5 * blk[0] + 40, 6 * blk[1] + 72, 7 * blk[2] + 24          # 42 tiles on 24 workgroups: 18 + 24
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 51)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for policy in (1, 2, 6):
+        for fixup in (sk.SK_FIXUP_FLAGS, sk.SK_FIXUP_ATOMIC):
+            _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True,
+                             fixup=fixup, launches=2, dp_first=True)

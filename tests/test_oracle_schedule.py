@@ -176,6 +176,26 @@ def test_policy_family_structure(shape, blk, g):
 
 
 @settings(max_examples=200, deadline=None)
+@given(shape_st, blk_st, grid_st, policy_st)
+def test_data_parallel_first_only_swaps_the_two_phases(shape, blk, g, policy):
+    # Sec. 3.2's earlier hybrid: same ranges, same segments per workgroup, data-parallel tiles in front
+    a = S.plan(*shape, policy, *blk, g)
+    b = S.plan(*shape, policy, *blk, g, dp_first=True)
+    assert b.header["dp_first"] and not a.header["dp_first"]
+    assert {k: v for k, v in a.header.items() if k != "dp_first"} == {k: v for k, v in b.header.items() if k != "dp_first"}
+    assert a.ranges == b.ranges
+    assert sorted(a.segments) == sorted(b.segments)
+    for x in range(g):
+        sa = [s for s in a.segments if s.wg == x]
+        sb = [s for s in b.segments if s.wg == x]
+        n_dp = a.ranges[x].dp_tile_count
+        n_sk = len(sa) - n_dp
+        assert sb == sa[n_sk:] + sa[:n_sk]
+        # under either order the data-parallel segments are whole tiles beyond the Stream-K region
+        assert all(s.role == S.ROLE_FULL and s.tile >= a.header["sk_tiles"] for s in sb[:n_dp])
+
+
+@settings(max_examples=200, deadline=None)
 @given(st.integers(1, 70), st.integers(1, 70))
 def test_tile_orders_are_bijections_onto_the_tile_grid(tiles_m, tiles_n):
     T = tiles_m * tiles_n
