@@ -455,26 +455,28 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         dm.init(g, m0, n0);
         // request batch j (issued after the barrier of stage j): B tile of stage j+NSB, then A tile of
         // stage j+NSA, into the slots of stage j; step / steps select a slice of the batch
-        auto issue_batch = [&](int j, int slot_a, int slot_b, int step, int steps) {
+        auto issue_batch = [&](int j, int slot_a, int slot_b, int step, int steps, auto steady) {
+            // steady: the caller knows that both stages exist and lie entirely inside K
+            constexpr bool STEADY = decltype(steady)::value;
             const int ib = j + C::NSB, ia = j + C::NSA;
             const int q0 = step * C::LPS / steps, q1 = (step + 1) * C::LPS / steps;
             const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
             const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
-            if (ib >= 0 && ib < nk && b1 > b0) {
+            if ((STEADY || (ib >= 0 && ib < nk)) && b1 > b0) {
                 const uint32_t lds = lds0 + C::B_RING + slot_b * C::B_BYTES;
-                if (k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
+                if (STEADY || k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
                 else dm.template issue_b<true>(g, k_begin + ib, lds, b0, b1);
             }
-            if (ia >= 0 && ia < nk && a1 > a0) {
+            if ((STEADY || (ia >= 0 && ia < nk)) && a1 > a0) {
                 const uint32_t lds = lds0 + slot_a * C::A_BYTES;
-                if (k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds, a0, a1);
+                if (STEADY || k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds, a0, a1);
                 else dm.template issue_a<true>(g, k_begin + ia, lds, a0, a1);
             }
         };
         // the batches that stages before the first would have requested, all but the last
 #pragma unroll
         for (int j = -C::NSA; j <= -2; j++)
-            issue_batch(j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
+            issue_batch(j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1, std::false_type());
         Frags<C> f[2];
         int ca = C::NSA - 1, cb = C::NSB - 1;        // ring slots of stage i (i = -1: the slots batch -1 fills)
         // one trip = [barrier that hands over stage i+1] [operands of stage i+1's first k-step]
@@ -486,19 +488,21 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         // bookkeeping merges conservatively at joins) - and scheduling barriers keep the reads of
         // k-step kk+1 ahead of the matrix-core work of k-step kk.  Otherwise the compiler is left
         // to order reads and matrix-core work so that one operand set suffices.
-        auto trip = [&](int i, auto first, auto next) {
+        auto trip = [&](int i, auto first, auto next, auto steady) {
             constexpr bool FIRST = decltype(first)::value;
+            constexpr bool STEADY = decltype(steady)::value;     // batch i's stages exist and need no K-tail handling, and at least NSA - 1 stages follow stage i + 1
             constexpr int NEXT = decltype(next)::value;          // 1 / 0: known, -1: decided at run time
             const bool has_next = NEXT < 0 ? i + 1 < nk : NEXT == 1;
             const int na = ca + 1 == C::NSA ? 0 : ca + 1, nb = cb + 1 == C::NSB ? 0 : cb + 1;   // slots of stage i+1
             const unsigned char* a_next = smem + na * C::A_BYTES;
             const unsigned char* b_next = smem + C::B_RING + nb * C::B_BYTES;
             if (has_next) {
-                wait_stage<C, C::NSA - 1>(nk - 2 - i);   // stage i+1 has landed (this wave's share)
+                if (STEADY) wait_vmcnt<C::in_flight(C::NSA - 1)>();
+                else wait_stage<C, C::NSA - 1>(nk - 2 - i);   // stage i+1 has landed (this wave's share)
                 __syncthreads();                         // ... and everybody's; stage i's slots are free
                 f[0].load(a_next, b_next, fm, 0);
             }
-            issue_batch(i, ca, cb, 0, C::KK);
+            issue_batch(i, ca, cb, 0, C::KK, steady);
             if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
             if (!FIRST) mma_step<C, TR>(f[1], acc);          // last k-step of stage i
             if (has_next) {
@@ -506,7 +510,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
                 for (int kk = 0; kk < C::KK - 1; kk++) {
                     if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
                     f[(kk + 1) & 1].load(a_next, b_next, fm, kk + 1);
-                    issue_batch(i, ca, cb, kk + 1, C::KK);
+                    issue_batch(i, ca, cb, kk + 1, C::KK, steady);
                     if (C::PIN_ORDER) __builtin_amdgcn_sched_barrier(0);
                     mma_step<C, TR>(f[kk & 1], acc);
                 }
@@ -517,13 +521,21 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         typedef std::integral_constant<int, 1> Yes;
         typedef std::integral_constant<int, 0> No;
         typedef std::integral_constant<int, -1> AtRunTime;
+        // Trips 0 .. n_steady-1 request stages that exist and lie inside K: their body carries neither
+        // range checks nor the K-tail variant of the requests, and waits with a constant count.
+        int n_steady = (full_k - k_begin < nk ? full_k - k_begin : nk) - C::NSA;
+        if (n_steady < 0) n_steady = 0;
         if (C::PIN_ORDER) {
-            trip(-1, std::true_type(), Yes());
-            for (int i = 0; i < nk - 1; i++) trip(i, std::false_type(), Yes());
-            trip(nk - 1, std::false_type(), No());
+            trip(-1, std::true_type(), Yes(), std::false_type());
+            int i = 0;
+            for (; i < n_steady; i++) trip(i, std::false_type(), Yes(), std::true_type());
+            for (; i < nk - 1; i++) trip(i, std::false_type(), Yes(), std::false_type());
+            trip(nk - 1, std::false_type(), No(), std::false_type());
         } else {
-            trip(-1, std::true_type(), AtRunTime());
-            for (int i = 0; i < nk; i++) trip(i, std::false_type(), AtRunTime());
+            trip(-1, std::true_type(), AtRunTime(), std::false_type());
+            int i = 0;
+            for (; i < n_steady; i++) trip(i, std::false_type(), Yes(), std::true_type());
+            for (; i < nk; i++) trip(i, std::false_type(), AtRunTime(), std::false_type());
         }
         __syncthreads();                             // all reads done before the next segment refills
     } else {
