@@ -1,0 +1,122 @@
+"""Fit the constants of the tile dispatcher's cost model (sk_default_tile) to timings.
+
+Input: one sweep file per tile shape, made with
+
+    python -m paper_2408_11417_amd.sweep --shapes 500 --seed 4 --skinny --tile 256,256,64 --out sweep_tile_256,256,64.json
+
+(the same sizes in every file).  The model predicts, for every tile shape, the time of the better
+of "whole tiles in waves" and "iterations split evenly plus partial-tile exchange"; the dispatcher
+picks the shape with the smallest prediction.  The fit minimises the regret of that pick (time under
+the picked shape / time under the fastest shape, best policy each) by random local search on a
+training split and reports it on the rest.  The constants are fitted for the quality of the pick,
+not for predicting times: they need not be physical (several parameter sets pick equally well).
+
+    python -m paper_2408_11417_amd.fit_tile_model sweep_tile_*.json
+
+Prints the constants in the order they appear in csrc/streamk_plan.cpp.  CPU only.
+"""
+import json
+import math
+import random
+import statistics
+import sys
+
+GRID, BK = 256, 64
+
+
+def cdiv(a, b):
+    return -(-a // b)
+
+
+def predict(P, tile, M, N, K):
+    """The cost model of sk_default_tile for one tile shape (microseconds)."""
+    bm, bn = tile
+    ipt = cdiv(K, BK)
+    T = cdiv(M, bm) * cdiv(N, bn)
+    t_iter = 2.0 * bm * bn * BK * GRID / (P["tflops"][tile] * 1e12) * 1e6
+    c_tile = P["tile_us"] + bm * bn * 2 / P["tile_bytes_per_us"]
+    t_dp = cdiv(T, GRID) * (ipt * t_iter + c_tile)
+    split = min(max(GRID / T, 1), ipt)
+    t_sk = cdiv(T * ipt, GRID) * t_iter + c_tile * max(T / GRID, 1.0)
+    if T % GRID:
+        # partial tiles an owner (or a group leader) fetches one after the other: all of them up to 16
+        # workgroups per tile, beyond that the two-level reduction with groups of 8
+        serial = split if split < 16 else 8 + split / 8
+        t_sk += P["part_us"] * (1 if split < 16 else 2) + serial * bm * bn * 4 / P["part_bytes_per_us"]
+    return min(t_dp, t_sk)
+
+
+def regrets(P, shapes, best, idx):
+    out = []
+    for j in idx:
+        pick = min(best, key=lambda t: predict(P, t, *shapes[j]))
+        out.append(best[pick][j] / min(best[t][j] for t in best))
+    return out
+
+
+def score(P, shapes, best, idx):
+    r = regrets(P, shapes, best, idx)
+    return statistics.mean(math.log(x) for x in r) + 0.5 * sum(x > 1.2 for x in r) / len(r)
+
+
+def describe(P, shapes, best, idx):
+    r = regrets(P, shapes, best, idx)
+    return "mean %.3f, worse than 1.1 on %.1f %%, worse than 1.2 on %.1f %%, max %.2f" % (
+        statistics.mean(r), 100 * sum(x > 1.1 for x in r) / len(r), 100 * sum(x > 1.2 for x in r) / len(r), max(r))
+
+
+def main():
+    files = sys.argv[1:]
+    if not files:
+        raise SystemExit(__doc__)
+    best, shapes = {}, None
+    for f in files:
+        recs = json.load(open(f))["records"]
+        tile = (recs[0]["tile"][0], recs[0]["tile"][1])
+        best[tile] = [min(r["time_ns"]) / 1000.0 for r in recs]
+        these = [(r["M"], r["N"], r["K"]) for r in recs]
+        assert shapes in (None, these), "the sweep files must cover the same sizes"
+        shapes = these
+    n = len(shapes)
+    idx = list(range(n))
+    random.Random(1).shuffle(idx)
+    train, test = idx[:4 * n // 5], idx[4 * n // 5:]
+    # the large skinny sizes are few among the random ones but matter (they are the HBM-bound workload): count them four times
+    train = train + [j for j in train if shapes[j][0] <= 128 and shapes[j][1] >= 4096 and shapes[j][2] >= 4096] * 3
+    start = {"tflops": {t: 4.4 * math.sqrt(t[0] * t[1]) for t in best}, "tile_us": 1.5, "tile_bytes_per_us": 50e3,
+             "part_us": 3.0, "part_bytes_per_us": 40e3}
+    fits = []
+    for seed in range(4):
+        rng = random.Random(10 + seed)
+        P = dict(start, tflops=dict(start["tflops"]))
+        s = score(P, shapes, best, train)
+        for _ in range(5000):
+            Q = dict(P, tflops=dict(P["tflops"]))
+            k = rng.choice(["tflops"] * 3 + ["tile_us", "tile_bytes_per_us", "part_us", "part_bytes_per_us"])
+            if k == "tflops":
+                t = rng.choice(list(best))
+                Q["tflops"][t] *= math.exp(rng.gauss(0, 0.12))
+            else:
+                Q[k] *= math.exp(rng.gauss(0, 0.2))
+            Q["part_us"] = min(max(Q["part_us"], 1.0), 40.0)
+            Q["tile_us"] = min(max(Q["tile_us"], 0.5), 10.0)
+            sq = score(Q, shapes, best, train)
+            if sq < s:
+                P, s = Q, sq
+        fits.append((score(P, shapes, best, test), P))
+        print("restart %d: train %s | held out %s" % (seed, describe(P, shapes, best, train), describe(P, shapes, best, test)))
+    # the restart that also does best on the held-out sizes
+    P = min(fits, key=lambda f: f[0])[1]
+    print("chosen: all sizes %s" % describe(P, shapes, best, idx))
+    for t in sorted(best, reverse=True):
+        print("  {%d, %d, %.0f.}," % (t[0], t[1], P["tflops"][t]))
+    print("  c_tile = %.2f + bm * bn * 2 / %.3g;  exchange = %.2f us per level + serial partial bytes / %.3g" % (
+        P["tile_us"], P["tile_bytes_per_us"], P["part_us"], P["part_bytes_per_us"]))
+    skinny = [j for j in idx if shapes[j][0] <= 128 and shapes[j][1] >= 4096 and shapes[j][2] >= 4096]
+    if skinny:
+        print("  skinny sizes (M <= 128, N and K >= 4096), %d of them: %s" % (len(skinny), describe(P, shapes, best, skinny)))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
