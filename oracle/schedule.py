@@ -41,6 +41,14 @@ R5  Tile index -> coordinates: row-major over the tile grid (order 0), or - beca
 R6  The workgroup whose segment holds a tile's k-iteration 0 owns the tile; the
     others store an fp32 partial in workspace slot = their workgroup id and the
     owner adds them in ascending workgroup order (= ascending k).
+R7  k_aligned=True is an execution order the paper does not have; it answers the
+    loss of cache locality that Sec. 5.3 remarks on.  Which workgroup runs which
+    iterations is Algorithm 1's, unchanged.  A workgroup whose range ends inside a
+    tile other than the one it starts in runs that last piece (k-iterations from 0)
+    first, then the rest of its range in ascending order, so all workgroups move
+    through k at about the same pace.  The owner of a split tile is then the
+    workgroup holding the tile's last k-iteration (it finishes last), and it adds
+    the partials of the others in descending workgroup order.
 """
 from collections import namedtuple
 
@@ -113,8 +121,12 @@ def wg_sk_range(x, sk_iters, iters_per_wg):
     return begin, end
 
 
-def wg_sk_segments(x, begin, end, iters_per_tile):
-    """Algorithm 1, the outer loop over a workgroup's range: cut [begin, end) at tile boundaries."""
+def wg_sk_segments(x, begin, end, iters_per_tile, k_aligned=False):
+    """Algorithm 1, the outer loop over a workgroup's range: cut [begin, end) at tile boundaries.
+
+    k_aligned (reading R7) moves a partial piece that starts at k-iteration 0 of a
+    later tile to the front, and hands the OWNER role to the piece that reaches
+    the tile's last iteration instead of the one that holds its first."""
     segs = []
     it = begin
     while it < end:
@@ -123,18 +135,20 @@ def wg_sk_segments(x, begin, end, iters_per_tile):
         tile_iter_end = tile_iter + iters_per_tile
         local_iter = it - tile_iter
         local_iter_end = min(end, tile_iter_end) - tile_iter
-        if local_iter > 0:
-            role = ROLE_CONTRIB
-        elif local_iter_end < iters_per_tile:
-            role = ROLE_OWNER
-        else:
+        if local_iter == 0 and local_iter_end == iters_per_tile:
             role = ROLE_FULL
+        elif k_aligned:
+            role = ROLE_OWNER if local_iter_end == iters_per_tile else ROLE_CONTRIB
+        else:
+            role = ROLE_OWNER if local_iter == 0 else ROLE_CONTRIB
         segs.append(Segment(x, tile, local_iter, local_iter_end, role))
         it = tile_iter_end
+    if k_aligned and len(segs) > 1 and segs[-1].k_end < iters_per_tile:
+        segs.insert(0, segs.pop())
     return segs
 
 
-def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_first=False):
+def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_first=False, k_aligned=False):
     """Full schedule for one problem: header, per-workgroup ranges, canonical segment list.
 
     The segment list is ordered by workgroup, and inside a workgroup in execution
@@ -142,7 +156,7 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_firs
     (Sec. 3.2 / 4.1: Stream-K batches come first).  dp_first=True swaps the two
     phases - the earlier hybrid that Sec. 3.2 describes, data-parallel batches
     followed by the Stream-K work; which tiles are split and which workgroup gets
-    which work does not change.
+    which work does not change.  k_aligned=True: reading R7.
     """
     if min(M, N, K, blk_m, blk_n, blk_k, g) < 1:
         raise ValueError("sizes must be positive")
@@ -156,7 +170,7 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_firs
     ranges, segments = [], []
     for x in range(g):
         begin, end = wg_sk_range(x, sk_iters, ipw)
-        sk_segs = wg_sk_segments(x, begin, end, ipt)
+        sk_segs = wg_sk_segments(x, begin, end, ipt, k_aligned)
         first = sk_tiles + x
         count = cdiv(tiles - first, g) if first < tiles else 0
         dp_segs = [Segment(x, first + j * g, 0, ipt, ROLE_FULL) for j in range(count)]
@@ -165,16 +179,22 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_firs
     header = dict(M=M, N=N, K=K, policy=policy, blk_m=blk_m, blk_n=blk_n, blk_k=blk_k, grid=g,
                   tiles_m=tiles_m, tiles_n=tiles_n, tiles=tiles, iters_per_tile=ipt,
                   total_iters=total, sk_tiles=sk_tiles, dp_tiles=dp_tiles, sk_iters=sk_iters,
-                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g), tile_order=order, dp_first=bool(dp_first))
+                  iters_per_wg=ipw, dp_waves=cdiv(dp_tiles, g), tile_order=order, dp_first=bool(dp_first),
+                  k_aligned=bool(k_aligned))
     return Plan(header, ranges, segments)
 
 
 def contributors(p, owner_segment):
-    """Workgroups whose partials the owner of a split tile adds, in reduction order (R6)."""
+    """Workgroups whose partials the owner of a split tile adds, in reduction order (R6, R7)."""
     ipt, ipw = p.header["iters_per_tile"], p.header["iters_per_wg"]
     assert owner_segment.role == ROLE_OWNER
+    first = (owner_segment.tile * ipt) // ipw
     last = (owner_segment.tile * ipt + ipt - 1) // ipw
-    return list(range(owner_segment.wg + 1, last + 1))
+    if p.header["k_aligned"]:
+        assert owner_segment.wg == last
+        return list(range(last - 1, first - 1, -1))
+    assert owner_segment.wg == first
+    return list(range(first + 1, last + 1))
 
 
 def makespan_iters(p):

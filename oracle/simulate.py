@@ -7,7 +7,7 @@ the workspace-and-flags fix-up (Sec. 5.3's alternative to the atomic adds at the
 end of Algorithm 1's loop body) computes the GEMM: every segment runs Algorithm 1's
 MAC_loop over its k-iterations into an fp32 accumulator tile; a
 CONTRIB segment parks its tile in the workspace slot of its workgroup; an OWNER
-adds the parked tiles of its contributors in ascending workgroup order and
+adds the parked tiles of its contributors in the schedule's reduction order and
 stores; a FULL segment stores directly.  Contributors always execute before the
 owner reads them here because the simulator runs all CONTRIB segments first;
 on the device the flags provide that ordering.
@@ -49,7 +49,7 @@ def run_plan(p, A, B):
             for c in S.contributors(p, seg):
                 tile, part = workspace.pop(c)
                 assert tile == seg.tile
-                acc = acc + part                   # fp32 add, ascending workgroup id
+                acc = acc + part                   # fp32 add, in reduction order
         D[r0:r1, c0:c1] = acc
         written[r0:r1, c0:c1] += 1
     assert not workspace, "unconsumed partial tiles"

@@ -31,9 +31,10 @@ SK_ROLE_FULL, SK_ROLE_OWNER, SK_ROLE_CONTRIB = 0, 1, 2
 SK_ORDER_ROW_MAJOR, SK_ORDER_GROUPED = 0, 1
 SK_FIXUP_FLAGS, SK_FIXUP_ATOMIC = 0, 1
 SK_STREAMK_FIRST, SK_DATA_PARALLEL_FIRST = 0, 1
+SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
-           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
+           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
            "sk_plan_destroy", "sk_default_tile", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
@@ -50,7 +51,8 @@ class sk_plan_header(ctypes.Structure):
                 ("tiles", ctypes.c_int32), ("iters_per_tile", ctypes.c_int32),
                 ("total_iters", ctypes.c_int64), ("sk_tiles", ctypes.c_int32), ("dp_tiles", ctypes.c_int32),
                 ("sk_iters", ctypes.c_int64), ("iters_per_wg", ctypes.c_int32), ("dp_waves", ctypes.c_int32),
-                ("has_kernel", ctypes.c_int32), ("tile_order", ctypes.c_int32)]
+                ("has_kernel", ctypes.c_int32), ("tile_order", ctypes.c_int32),
+                ("fixup", ctypes.c_int32), ("batch_order", ctypes.c_int32), ("segment_order", ctypes.c_int32)]
 
 
 class sk_wg_range(ctypes.Structure):
@@ -82,6 +84,7 @@ _lib.sk_plan_set_workspace.argtypes = [_vp, _vp, ctypes.c_size_t]
 _lib.sk_plan_set_spin_limit.argtypes = [_vp, ctypes.c_uint32]
 _lib.sk_plan_set_fixup.argtypes = [_vp, _int]
 _lib.sk_plan_set_batch_order.argtypes = [_vp, _int]
+_lib.sk_plan_set_segment_order.argtypes = [_vp, _int]
 _lib.sk_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sk_plan_check.argtypes = [_vp, _vp]
 _lib.sk_plan_destroy.argtypes = [_vp]
@@ -178,6 +181,10 @@ def sk_plan_set_fixup(plan, fixup):
 
 def sk_plan_set_batch_order(plan, batch_order):
     _check(_lib.sk_plan_set_batch_order(plan, batch_order), "sk_plan_set_batch_order")
+
+
+def sk_plan_set_segment_order(plan, segment_order):
+    _check(_lib.sk_plan_set_segment_order(plan, segment_order), "sk_plan_set_segment_order")
 
 
 def sk_plan_set_spin_limit(plan, polls):

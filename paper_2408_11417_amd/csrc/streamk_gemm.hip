@@ -137,8 +137,9 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.spin_limit = plan->spin_limit;
     g.out_dtype = h.out_dtype;
     g.dp_first = plan->dp_first;
+    g.k_aligned = plan->k_aligned;
     if (atomic) {
-        // Algorithm 1, lines 14-18 need C to start at zero: clear the image in-stream, accumulate, convert
+        // Algorithm 1's atomic accumulation needs C to start at zero: clear the image in-stream, accumulate, convert
         const size_t n = (size_t)h.M * (size_t)h.N;
         g.image = h.out_dtype == SK_F32 ? static_cast<float*>(D) : g.partials;
         const int blocks = (int)((n / 4 + 255) / 256 < 2048 ? (n / 4 + 255) / 256 : 2048);

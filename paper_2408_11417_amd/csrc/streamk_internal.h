@@ -12,6 +12,7 @@ struct sk_plan_t {
     int needs_fixup = 0;            // 1 if any tile is split over several workgroups
     int fixup = SK_FIXUP_FLAGS;     // how split tiles are combined
     int dp_first = 0;               // 1: data-parallel tiles before the Stream-K iterations
+    int k_aligned = 1;              // 1: head piece of a Stream-K range first, last workgroup of a tile owns it
 };
 
 // Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]

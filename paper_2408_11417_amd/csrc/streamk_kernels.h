@@ -1,6 +1,6 @@
 // Stream-K GEMM for gfx950 (MI355X): one persistent kernel serves every
 // scheduling policy.  Each workgroup derives its own share of the iteration
-// space from a handful of plan numbers (Algorithm 1, lines 4-12), runs the MAC
+// space from a handful of plan numbers (Algorithm 1's range and tile arithmetic), runs the MAC
 // loop of each segment on the matrix cores, and either stores the tile, parks an
 // fp32 partial in the workspace, or - as the tile's owner - waits for the parked
 // partials and adds them in a fixed order (the synchronised reduction that
@@ -47,6 +47,8 @@ struct GemmArgs {
     uint32_t spin_limit;
     int out_dtype;
     int dp_first;          // 1: a workgroup runs its data-parallel tiles before its Stream-K iterations
+    int k_aligned;         // 1: a workgroup runs the head of its last Stream-K tile (k from 0) before the tail of its
+                           //    first one, and the workgroup holding a tile's last iteration reduces and stores it
 };
 
 // ---- matrix-core wrappers ---------------------------------------------------------------------
@@ -434,7 +436,7 @@ __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const un
     }
 }
 
-// MAC loop of one segment (Algorithm 1, line 13): k-iterations [k_begin, k_end) of one tile.
+// MAC loop of one segment (Algorithm 1's MAC-loop call): k-iterations [k_begin, k_end) of one tile.
 //
 // Software pipeline of the LDS-DMA path.  Stage s (one k-iteration) lives in A ring slot s % NSA and
 // B ring slot s % NSB.  The barrier that hands stage i+1 to the waves sits one k-step *before* the
@@ -590,7 +592,7 @@ __device__ __forceinline__ void wait_flags(const GemmArgs& g, int first, int cou
 // that order.  For tiles with at most 64 accumulators per lane: a contributor's whole share is
 // fetched at once and G contributors per round trip (about 64 registers of loads in flight).
 template <class C>
-__device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&sum)[C::MI][C::NI], const float* src, int count, size_t stride) {
+__device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&sum)[C::MI][C::NI], const float* src, int count, ptrdiff_t stride) {
     constexpr int G = 64 / C::ACC_REGS < 8 ? 64 / C::ACC_REGS : 8;
     auto add_group = [&](const float* p, auto cnt) {
         constexpr int CNT = decltype(cnt)::value;
@@ -686,13 +688,13 @@ __device__ __forceinline__ void store_block(const GemmArgs& g, int row, int col0
 }
 
 // Epilogue of a tile's owner (or of an unsplit tile, n_contrib = 0): add the parked partials of the
-// contributors part0, part0 + part_stride, ... (ascending workgroup order = ascending k), convert and store.  OUT selects the
+// contributors part0, part0 + part_stride, ... (a fixed order: away from the owner in k), convert and store.  OUT selects the
 // output type, EDGE adds the bounds checks, TR says that the blocks are transposed (see store_block).
 // row0 / col0: the lane's (first) row and (first) column in the wave's first block.  The big tiles
 // work one block at a time, which keeps their register need flat.
 template <class C, int OUT, bool EDGE, bool TR>
 __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, int col0, const float* part0, int n_contrib,
-                                                 size_t part_stride, const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+                                                 ptrdiff_t part_stride, const typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
     // Tiles with few accumulators per lane fetch a contributor's whole share at once (one round trip
     // per contributor instead of one per block and contributor); the big tiles have no registers for that.
@@ -730,7 +732,7 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
         }
 }
 
-// Atomic fix-up (Algorithm 1, lines 14-18): a segment that covers only part of the tile's
+// Atomic fix-up (the accumulation step of Algorithm 1): a segment that covers only part of the tile's
 // K-iterations adds its accumulators into the zero-initialised fp32 image with atomic adds; a
 // segment that covers the whole tile stores them.  Blocks are not transposed here: the lanes of
 // one atomic instruction then sit side by side in a row of the image (two cache lines per
@@ -769,16 +771,31 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     FragMap<C> fm;
     fm.init();
 
-    // Algorithm 1, lines 5-6 (clamped): this workgroup's share of the Stream-K iterations
+    // Algorithm 1 (clamped): this workgroup's share of the Stream-K iterations
     int it = x * g.ipw, it_end = it + g.ipw;
     if (it > g.sk_iters) it = g.sk_iters;
     if (it_end > g.sk_iters) it_end = g.sk_iters;
     int dp_tile = g.sk_tiles + x;   // data-parallel tiles come after the Stream-K work
+    // k-aligned order: a share that ends inside a tile other than the one it starts in gives up that
+    // head piece (k from 0) to be run first; the rest - the tail of the first tile, then whole
+    // tiles - follows in ascending order.  Workgroups then walk through k at nearly the same pace
+    // whatever their offset in the iteration space, which keeps the operand blocks they share in L2.
+    int head_tile = 0, head_k_end = 0;
+    if (g.k_aligned && it < it_end) {
+        const int last_tile = (int)((uint32_t)(it_end - 1) / (uint32_t)g.ipt);
+        const int last_first = last_tile * g.ipt;
+        if (last_first > it && it_end < last_first + g.ipt) {
+            head_tile = last_tile; head_k_end = it_end - last_first; it_end = last_first;
+        }
+    }
 
     while (true) {
         int tile, k_begin, k_end;
-        const bool dp_now = dp_tile < g.tiles && (g.dp_first || it >= it_end);
-        if (!dp_now && it < it_end) {            // Algorithm 1, lines 8-12
+        const bool dp_now = dp_tile < g.tiles && (g.dp_first || (head_k_end == 0 && it >= it_end));
+        if (!dp_now && head_k_end > 0) {
+            tile = head_tile; k_begin = 0; k_end = head_k_end;
+            head_k_end = 0;
+        } else if (!dp_now && it < it_end) {     // Algorithm 1: cut the share at tile boundaries
             tile = (int)((uint32_t)it / (uint32_t)g.ipt);
             const int tile_first = tile * g.ipt;
             k_begin = it - tile_first;
@@ -826,24 +843,31 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         // big ones never have that many contributors): every SK_TREE_GROUP-th contributor first
         // adds the partials of the contributors behind it to its own accumulators, so the owner
         // collects one partial per group.  The order of the additions stays fixed.
+        // The owner of a split tile is the workgroup holding its first iteration, the contributors
+        // are the workgroups after it (dir = +1); in the k-aligned order the one holding its last
+        // iteration, which finishes last, and the contributors are the workgroups before it (dir = -1).
         constexpr bool TREE = C::ACC_REGS <= 64;
-        int tile_first_wg = 0, n_all = 0;                               // the tile's owner, its number of contributors
-        if (k_begin > 0 || k_end < g.ipt) {                             // (only split tiles; ipw is 0 in a plan without Stream-K work)
-            tile_first_wg = (int)((uint32_t)(tile * g.ipt) / (uint32_t)g.ipw);
-            n_all = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw) - tile_first_wg;
+        const bool split = k_begin > 0 || k_end < g.ipt;
+        const bool contributor = g.k_aligned ? k_end < g.ipt : k_begin > 0;
+        const int dir = g.k_aligned ? -1 : 1;
+        int j = 0, n_all = 0;                                           // distance from the tile's owner, the tile's number of contributors
+        if (split) {                                                    // (only split tiles; ipw is 0 in a plan without Stream-K work)
+            const int first_wg = (int)((uint32_t)(tile * g.ipt) / (uint32_t)g.ipw);
+            const int last_wg = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
+            n_all = last_wg - first_wg;
+            j = g.k_aligned ? last_wg - x : x - first_wg;
         }
         const bool two_level = TREE && n_all >= 2 * SK_TREE_GROUP;
-        if (k_begin > 0) {
-            // contributor
+        const ptrdiff_t slot_stride = (ptrdiff_t)dir * (C::BM * C::BN);
+        if (contributor) {
             if constexpr (TREE) {
-                const int j = x - tile_first_wg;                        // 1 .. n_all
                 if (two_level && (j - 1) % SK_TREE_GROUP == 0) {        // group leader: members j+1 .. j+GROUP-1
                     const int members = (j + SK_TREE_GROUP - 1 <= n_all ? j + SK_TREE_GROUP - 1 : n_all) - j;
-                    if (wave == 0) wait_flags(g, x + 1, members, 1);
+                    if (wave == 0) wait_flags(g, x + dir, members, dir);
                     __syncthreads();
-                    const float* mp = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
+                    const float* mp = g.partials + (ptrdiff_t)(x + dir) * (C::BM * C::BN) + tid;
                     asm volatile("" : "+v"(mp));
-                    add_partials<C>(acc, mp, members, (size_t)(C::BM * C::BN));
+                    add_partials<C>(acc, mp, members, slot_stride);
                 }
             }
             // park the accumulators (register order, coalesced), then signal.
@@ -871,16 +895,15 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             continue;
         }
         int n_contrib = 0;
-        size_t part_stride = (size_t)(C::BM * C::BN);
-        if (k_end < g.ipt) {
-            // owner (x == tile_first_wg): contributors are the following workgroups up to the one
-            // holding the tile's last iteration - or, with two levels, their group leaders.  Wait for
-            // all of them; the epilogue adds their partials in a fixed order, so the result does
-            // not depend on timing.
+        ptrdiff_t part_stride = slot_stride;
+        if (split) {
+            // owner: the contributors are the n_all workgroups next to it in direction dir - or, with
+            // two levels, their group leaders.  Wait for all of them; the epilogue adds their
+            // partials in a fixed order, so the result does not depend on timing.
             const int step = two_level ? SK_TREE_GROUP : 1;
             n_contrib = (n_all + step - 1) / step;
             part_stride *= step;
-            if (wave == 0) wait_flags(g, x + 1, n_contrib, step);
+            if (wave == 0) wait_flags(g, x + dir, n_contrib, step * dir);
             __syncthreads();
         }
 
@@ -888,7 +911,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         int row0 = m0 + wm * C::WTM + (TR ? lane % C::MF : 4 * (lane / C::MF));
         int col0 = n0 + wn * C::WTN + (TR ? 4 * (lane / C::MF) : lane % C::MF);
         asm volatile("" : "+v"(row0), "+v"(col0));
-        const float* part0 = g.partials + (size_t)(x + 1) * (C::BM * C::BN) + tid;
+        const float* part0 = g.partials + (ptrdiff_t)(x + dir) * (C::BM * C::BN) + tid;
         asm volatile("" : "+v"(part0));
         const bool edge = m0 + C::BM > g.M || n0 + C::BN > g.N;
         if (g.out_dtype == SK_BF16) {

@@ -25,7 +25,8 @@ bool dtype_in_ok(int d) { return d == SK_F16 || d == SK_BF16 || d == SK_FP8_E4M3
 bool dtype_out_ok(int d) { return d == SK_F16 || d == SK_BF16 || d == SK_F32; }
 
 // Segments of workgroup x, appended in execution order.
-void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_wg_range* range, bool dp_first = false) {
+void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_wg_range* range, bool dp_first = false,
+               bool k_aligned = false) {
     const int64_t ipt = h.iters_per_tile;
     int64_t it = x * (int64_t)h.iters_per_wg;
     int64_t end = it + h.iters_per_wg;
@@ -33,7 +34,22 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
     if (end > h.sk_iters) end = h.sk_iters;
     if (range) { range->sk_iter_begin = it; range->sk_iter_end = end; }
     const size_t at = out ? out->size() : 0;     // where this workgroup's segments start
-    // Algorithm 1, lines 7-20: one segment per tile the range touches
+    auto role_of = [&](const sk_segment& s) {
+        if (s.k_begin == 0 && s.k_end == ipt) return SK_ROLE_FULL;
+        const bool contributor = k_aligned ? s.k_end < ipt : s.k_begin > 0;
+        return contributor ? SK_ROLE_CONTRIB : SK_ROLE_OWNER;
+    };
+    if (k_aligned && it < end) {
+        // a range that ends inside another tile than it starts in runs that head piece first
+        const int64_t last_tile = (end - 1) / ipt, last_first = last_tile * ipt;
+        if (last_first > it && end < last_first + ipt) {
+            sk_segment s{x, (int32_t)last_tile, 0, (int32_t)(end - last_first), 0};
+            s.role = role_of(s);
+            if (out) out->push_back(s);
+            end = last_first;
+        }
+    }
+    // Algorithm 1, outer loop: one segment per tile the range touches
     while (it < end) {
         const int64_t tile = it / ipt;
         const int64_t tile_first = tile * ipt;
@@ -43,7 +59,7 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
         s.tile = (int32_t)tile;
         s.k_begin = (int32_t)(it - tile_first);
         s.k_end = (int32_t)(stop - tile_first);
-        s.role = s.k_begin > 0 ? SK_ROLE_CONTRIB : (s.k_end < ipt ? SK_ROLE_OWNER : SK_ROLE_FULL);
+        s.role = role_of(s);
         if (out) out->push_back(s);
         it = tile_first + ipt;
     }
@@ -135,7 +151,7 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
     h.M = M; h.N = N; h.K = K; h.policy = policy;
     h.blk_m = blk[0]; h.blk_n = blk[1]; h.blk_k = blk[2]; h.grid = grid;
     h.in_dtype = in_dtype; h.out_dtype = out_dtype;
-    // Algorithm 1, lines 2-3
+    // Algorithm 1: iterations per tile, total iterations
     const int64_t tiles_m = ceil_div(M, blk[0]), tiles_n = ceil_div(N, blk[1]);
     const int64_t ipt = ceil_div(K, blk[2]);
     const int64_t tiles = tiles_m * tiles_n;
@@ -159,10 +175,13 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
     // (data-parallel) work gain from the compact blocks of the grouped order.
     if (order < 0) order = (sk_tiles == tiles) ? SK_ORDER_ROW_MAJOR : SK_ORDER_GROUPED;
     h.tile_order = order;
+    h.fixup = SK_FIXUP_FLAGS;
+    h.batch_order = SK_STREAMK_FIRST;
+    h.segment_order = SK_SEGMENTS_K_ALIGNED;
     h.sk_tiles = (int32_t)sk_tiles;
     h.dp_tiles = (int32_t)(tiles - sk_tiles);
     h.sk_iters = sk_tiles * ipt;
-    const int64_t ipw = ceil_div(h.sk_iters, grid);   // Algorithm 1, line 4, on the split region
+    const int64_t ipw = ceil_div(h.sk_iters, grid);   // Algorithm 1: iterations per workgroup, on the split region
     if (ipw > imax) return SK_ERR_INVALID_ARG;
     h.iters_per_wg = (int32_t)ipw;
     h.dp_waves = (int32_t)ceil_div(h.dp_tiles, grid);
@@ -193,7 +212,7 @@ extern "C" int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t c
     if (!plan || !n || (!out && cap)) return SK_ERR_INVALID_ARG;
     std::vector<sk_segment> segs;
     try {
-        for (int x = 0; x < plan->h.grid; x++) expand_wg(plan->h, x, &segs, nullptr, plan->dp_first != 0);
+        for (int x = 0; x < plan->h.grid; x++) expand_wg(plan->h, x, &segs, nullptr, plan->dp_first != 0, plan->k_aligned != 0);
     } catch (const std::bad_alloc&) {
         return SK_ERR_NOMEM;
     }
@@ -247,12 +266,21 @@ extern "C" size_t sk_workspace_bytes(const sk_plan_t* plan) {
 extern "C" int sk_plan_set_fixup(sk_plan_t* plan, int fixup) {
     if (!plan || (fixup != SK_FIXUP_FLAGS && fixup != SK_FIXUP_ATOMIC) || plan->workspace) return SK_ERR_INVALID_ARG;
     plan->fixup = fixup;
+    plan->h.fixup = fixup;
     return SK_OK;
 }
 
 extern "C" int sk_plan_set_batch_order(sk_plan_t* plan, int batch_order) {
     if (!plan || (batch_order != SK_STREAMK_FIRST && batch_order != SK_DATA_PARALLEL_FIRST)) return SK_ERR_INVALID_ARG;
     plan->dp_first = batch_order == SK_DATA_PARALLEL_FIRST;
+    plan->h.batch_order = batch_order;
+    return SK_OK;
+}
+
+extern "C" int sk_plan_set_segment_order(sk_plan_t* plan, int segment_order) {
+    if (!plan || (segment_order != SK_SEGMENTS_ASCENDING && segment_order != SK_SEGMENTS_K_ALIGNED)) return SK_ERR_INVALID_ARG;
+    plan->k_aligned = segment_order == SK_SEGMENTS_K_ALIGNED;
+    plan->h.segment_order = segment_order;
     return SK_OK;
 }
 

@@ -35,7 +35,7 @@ def time_policy(sk, torch, plan, sets, stream, est_ms):
     return e0.elapsed_time(e1) / reps, reps
 
 
-def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False):
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False):
     import torch
     import paper_2408_11417_amd as sk
 
@@ -73,6 +73,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
             sk.sk_plan_set_fixup(plan, fixup)
             if dp_first:
                 sk.sk_plan_set_batch_order(plan, sk.SK_DATA_PARALLEL_FIRST)
+            if ascending:
+                sk.sk_plan_set_segment_order(plan, sk.SK_SEGMENTS_ASCENDING)
             assert sk.sk_workspace_bytes(plan) <= ws_bytes
             sk.sk_plan_set_workspace(plan, ws_ptr, ws_bytes)
             plans.append(plan)
@@ -119,7 +121,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
         if out_path and (idx % 50 == 49 or idx == len(shapes) - 1):
             with open(out_path, "w") as f:
                 json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256,
-                           "fixup": "atomic" if fixup else "flags", "dp_first": bool(dp_first), "records": records}, f)
+                           "fixup": "atomic" if fixup else "flags", "dp_first": bool(dp_first),
+                           "segment_order": "ascending" if ascending else "k_aligned", "records": records}, f)
     return records
 
 
@@ -134,8 +137,10 @@ def main():
                     help="append the skinny family (M in 16..128, N = K in 4096, 8192; N = 16384, K = 4096) to the shapes")
     ap.add_argument("--dp-first", action="store_true",
                     help="data-parallel batches before the Stream-K work (the earlier hybrid of Sec. 3.2)")
+    ap.add_argument("--ascending", action="store_true",
+                    help="Algorithm 1's order of a workgroup's Stream-K pieces instead of the k-aligned default")
     ap.add_argument("--fixup", choices=("flags", "atomic"), default="flags",
-                    help="how split tiles are combined (atomic = Algorithm 1, lines 14-18)")
+                    help="how split tiles are combined (atomic = Algorithm 1's accumulation into C)")
     args = ap.parse_args()
     from paper_2408_11417_amd import inputs
     shapes = inputs.sweep_shapes(args.shapes, args.seed)
@@ -144,7 +149,7 @@ def main():
     if args.skinny:
         shapes += [(M, N, K) for M in (16, 32, 64, 128) for N, K in ((8192, 8192), (4096, 4096), (16384, 4096))]
     tile = tuple(int(v) for v in args.tile.split(",")) if args.tile else None
-    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0, tile=tile, dp_first=args.dp_first)
+    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0, tile=tile, dp_first=args.dp_first, ascending=args.ascending)
     return 0
 
 

@@ -20,17 +20,18 @@ ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16, inputs.E4M3: G.E4M3}
 
 
 def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False,
-                     fixup=sk.SK_FIXUP_FLAGS, launches=1, dp_first=False):
+                     fixup=sk.SK_FIXUP_FLAGS, launches=1, dp_first=False, k_aligned=True):
     M, K = A.shape
     N = B.shape[1]
-    print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s fixup=%d" %
-          (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype, fixup), flush=True)
-    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup, dp_first=dp_first)
+    print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s fixup=%d dp_first=%d k_aligned=%d" %
+          (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype, fixup, dp_first, k_aligned), flush=True)
+    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup, dp_first=dp_first, k_aligned=k_aligned)
     try:
         # the library's schedule for this very launch equals the oracle's
         o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"], r.info["tile_order"],
-                   dp_first=dp_first)
+                   dp_first=dp_first, k_aligned=k_aligned)
         assert sk.sk_plan_segments(r.plan) == [tuple(s) for s in o.segments]
+        assert r.info["segment_order"] == int(k_aligned) and r.info["batch_order"] == int(dp_first) and r.info["fixup"] == fixup
         dA, dB = to_device(A), to_device(B)
         for _ in range(launches):
             r.run(dA, dB)
@@ -306,3 +307,45 @@ def test_data_parallel_batches_first(blk):
         for fixup in (sk.SK_FIXUP_FLAGS, sk.SK_FIXUP_ATOMIC):
             _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True,
                              fixup=fixup, launches=2, dp_first=True)
+
+
+# ---- Algorithm 1's own segment order (ascending iterations, the first workgroup of a tile owns it); every
+# ---- other test runs the library's default, the k-aligned order ----------------------------------
+
+@pytest.mark.parametrize("blk", [(128, 128, 64), (256, 128, 64), (256, 256, 64), (64, 128, 64), (32, 128, 64), (16, 128, 64)])
+def test_ascending_order_integer_exact(blk):
+    # 42 tiles on 24 workgroups (two pieces per workgroup, hybrids and all-Stream-K), both batch orders, both fix-ups
+    M, N, K = 5 * blk[0] + 40, 6 * blk[1] + 72, 7 * blk[2] + 24
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 61)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for policy in (1, 2, 3, 6):
+        for fixup in (sk.SK_FIXUP_FLAGS, sk.SK_FIXUP_ATOMIC):
+            _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True,
+                             fixup=fixup, launches=2, dp_first=policy == 2, k_aligned=False)
+
+
+@pytest.mark.parametrize("shape,blk,grid", [
+    ((64, 208, 7872), (32, 128, 64), 256),      # 4 tiles, ~64 workgroups each: two-level reduction
+    ((100, 128, 40000), (16, 128, 64), 200),    # 7 tiles, ragged groups
+    ((128, 256, 4096), (64, 128, 64), 37),      # 4 tiles over 37 workgroups: flat reduction with 9-10 contributors
+    ((512, 512, 512), (128, 128, 32), 256),     # cfg1's shape: 16 workgroups per tile, one iteration each
+])
+def test_ascending_order_tiles_shared_by_many_workgroups(shape, blk, grid):
+    M, N, K = shape
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 62)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_ALL_SK, blk, grid=grid, out_dtype=sk.SK_F32, ref=ref, exact=True,
+                     launches=3, k_aligned=False)
+    A, B = inputs.uniform_pair(M, N, K, inputs.BF16, 63)
+    _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_ALL_SK, blk, grid=grid, launches=2, k_aligned=False)
+
+
+def test_ascending_order_config2_rows_and_fp8():
+    c = inputs.config2()
+    rows = inputs.sample_rows(c["M"], 24, 9)
+    ref = G.gemm_fp64(c["A"], c["B"], G.BF16, rows=rows)
+    for policy in (1, 3, 6):
+        _run_and_compare(c["A"], c["B"], inputs.BF16, policy, c["blk"], c["grid"], rows=rows, ref=ref, k_aligned=False)
+    A, B = inputs.uniform_pair(1000, 1100, 2100, inputs.E4M3, 64)
+    for policy in (1, 6):
+        _run_and_compare(A, B, inputs.E4M3, policy, (256, 256, 128), 24, k_aligned=False)

@@ -25,13 +25,20 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
-def _plan_pair(M, N, K, policy, blk, g, order=None, dp_first=False):
+def _plan_pair(M, N, K, policy, blk, g, order=None, dp_first=False, k_aligned=None):
     p = sk.sk_plan(M, N, K, policy, blk, g, tile_order=order)
     try:
+        assert sk.sk_plan_info(p)["segment_order"] == sk.SK_SEGMENTS_K_ALIGNED        # the library's default
+        assert sk.sk_plan_info(p)["batch_order"] == sk.SK_STREAMK_FIRST and sk.sk_plan_info(p)["fixup"] == sk.SK_FIXUP_FLAGS
         if dp_first:
             sk.sk_plan_set_batch_order(p, sk.SK_DATA_PARALLEL_FIRST)
+        if k_aligned is not None:
+            sk.sk_plan_set_segment_order(p, sk.SK_SEGMENTS_K_ALIGNED if k_aligned else sk.SK_SEGMENTS_ASCENDING)
+        else:
+            k_aligned = True
         info = sk.sk_plan_info(p)
-        o = S.plan(M, N, K, policy, *blk, g, order=info["tile_order"], dp_first=dp_first)
+        assert info["segment_order"] == int(k_aligned) and info["batch_order"] == int(dp_first)
+        o = S.plan(M, N, K, policy, *blk, g, order=info["tile_order"], dp_first=dp_first, k_aligned=k_aligned)
         step = max(1, info["tiles"] // 500)
         for t in list(range(0, info["tiles"], step)) + [info["tiles"] - 1]:
             assert sk.sk_plan_tile_coords(p, t) == S.tile_coords(t, info["tiles_m"], info["tiles_n"], info["tile_order"])
@@ -54,7 +61,8 @@ def _assert_same(info, ranges, segs, o):
                  st.sampled_from([8, 32, 64, 128])),
        st.sampled_from([1, 2, 3, 7, 8, 64, 104, 256, 304]), st.integers(0, 7))
 def test_schedule_bit_exact_random(shape, blk, g, policy):
-    _assert_same(*_plan_pair(*shape, policy, blk, g, order=(shape[0] + policy) % 2, dp_first=shape[1] % 3 == 0))
+    _assert_same(*_plan_pair(*shape, policy, blk, g, order=(shape[0] + policy) % 2, dp_first=shape[1] % 3 == 0,
+                             k_aligned=shape[2] % 2 == 0))
 
 
 @pytest.mark.parametrize("policy", range(8))
@@ -130,11 +138,13 @@ def test_fixup_mode_setter_and_workspace_need():
     import ctypes
     lib = sk.binding._lib
     assert lib.sk_plan_set_batch_order(None, 0) == sk.SK_ERR_INVALID_ARG
+    assert lib.sk_plan_set_segment_order(None, 0) == sk.SK_ERR_INVALID_ARG
     p = sk.sk_plan(512, 384, 512, sk.SK_POLICY_ALL_SK, (128, 128, 32), 256, sk.SK_F16)
     flags_bytes = sk.sk_workspace_bytes(p)
     assert flags_bytes >= 256 * 128 * 128 * 4
     assert lib.sk_plan_set_fixup(p, 2) == sk.SK_ERR_INVALID_ARG
     assert lib.sk_plan_set_batch_order(p, 2) == sk.SK_ERR_INVALID_ARG
+    assert lib.sk_plan_set_segment_order(p, 2) == sk.SK_ERR_INVALID_ARG
     assert lib.sk_plan_set_fixup(None, 0) == sk.SK_ERR_INVALID_ARG
     sk.sk_plan_set_fixup(p, sk.SK_FIXUP_ATOMIC)
     # atomic mode with a 16-bit output: flag / status lines + an fp32 image of D

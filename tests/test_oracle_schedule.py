@@ -195,6 +195,63 @@ def test_data_parallel_first_only_swaps_the_two_phases(shape, blk, g, policy):
         assert all(s.role == S.ROLE_FULL and s.tile >= a.header["sk_tiles"] for s in sb[:n_dp])
 
 
+@settings(max_examples=300, deadline=None)
+@given(shape_st, blk_st, grid_st, policy_st, st.booleans())
+def test_k_aligned_order_keeps_the_work_and_moves_head_and_owner(shape, blk, g, policy, dp_first):
+    # same iterations per workgroup as Algorithm 1; only the order inside a workgroup and the owner change
+    a = S.plan(*shape, policy, *blk, g, dp_first=dp_first)
+    b = S.plan(*shape, policy, *blk, g, dp_first=dp_first, k_aligned=True)
+    ipt = a.header["iters_per_tile"]
+    assert a.ranges == b.ranges
+    strip = lambda segs: sorted(s[:4] for s in segs)                      # noqa: E731
+    assert strip(a.segments) == strip(b.segments)
+    pieces = {}
+    for s in b.segments:
+        pieces.setdefault(s.tile, []).append(s)
+    for tile, ps in pieces.items():
+        ps.sort(key=lambda s: s.k_begin)
+        assert ps[0].k_begin == 0 and ps[-1].k_end == ipt
+        assert all(x.k_end == y.k_begin for x, y in zip(ps, ps[1:]))     # the tile's k-range, cut without gaps
+        if len(ps) == 1:
+            assert ps[0].role == S.ROLE_FULL
+            continue
+        assert [s.role for s in ps] == [S.ROLE_CONTRIB] * (len(ps) - 1) + [S.ROLE_OWNER]   # the last piece owns
+        assert S.contributors(b, ps[-1]) == [s.wg for s in ps[-2::-1]]   # the others, nearest first
+        assert [s.wg for s in ps] == list(range(ps[0].wg, ps[0].wg + len(ps)))
+    for x in range(g):
+        sa = [s[:4] for s in a.segments if s.wg == x and s.tile < a.header["sk_tiles"]]
+        sb = [s[:4] for s in b.segments if s.wg == x and s.tile < a.header["sk_tiles"]]
+        if len(sa) > 1 and sa[-1][3] < ipt:
+            assert sb == [sa[-1]] + sa[:-1]                               # the head piece moved to the front
+            assert sb[0][2] == 0
+        else:
+            assert sb == sa
+        # pace: a workgroup with a head and a tail piece walks k upwards with one jump of ipt - (its two pieces' length)
+        if len(sb) >= 2 and sb[0][3] < ipt and sb[1][2] > 0 and sb[0][1] != sb[1][1]:
+            assert sb[1][2] - sb[0][3] == ipt - ((sb[0][3] - sb[0][2]) + (sb[1][3] - sb[1][2]))
+
+
+def test_k_aligned_worked_example():
+    # 5 tiles of 8 iterations over 4 workgroups, all Stream-K: 10 iterations each.
+    #   wg0: tile0 [0,8) whole, tile1 [0,2)        -> head first: tile1 [0,2) CONTRIB, tile0 FULL
+    #   wg1: tile1 [2,8), tile2 [0,4)              -> tile2 [0,4) CONTRIB, tile1 [2,8) OWNER
+    #   wg2: tile2 [4,8), tile3 [0,6)              -> tile3 [0,6) CONTRIB, tile2 [4,8) OWNER
+    #   wg3: tile3 [6,8), tile4 [0,8) whole        -> tile3 [6,8) OWNER, tile4 FULL
+    p = S.plan(40, 8, 64, S.POLICY_ALL_SK, 8, 8, 8, 4, k_aligned=True)
+    C, O, F = S.ROLE_CONTRIB, S.ROLE_OWNER, S.ROLE_FULL
+    assert [tuple(s) for s in p.segments] == [
+        (0, 1, 0, 2, C), (0, 0, 0, 8, F),
+        (1, 2, 0, 4, C), (1, 1, 2, 8, O),
+        (2, 3, 0, 6, C), (2, 2, 4, 8, O),
+        (3, 3, 6, 8, O), (3, 4, 0, 8, F)]
+    q = S.plan(40, 8, 64, S.POLICY_ALL_SK, 8, 8, 8, 4)
+    assert [tuple(s) for s in q.segments] == [
+        (0, 0, 0, 8, F), (0, 1, 0, 2, O),
+        (1, 1, 2, 8, C), (1, 2, 0, 4, O),
+        (2, 2, 4, 8, C), (2, 3, 0, 6, O),
+        (3, 3, 6, 8, C), (3, 4, 0, 8, F)]
+
+
 @settings(max_examples=200, deadline=None)
 @given(st.integers(1, 70), st.integers(1, 70))
 def test_tile_orders_are_bijections_onto_the_tile_grid(tiles_m, tiles_n):
@@ -233,8 +290,9 @@ def test_executed_schedule_equals_bruteforce_16cubed(policy):
     A, B = inputs.small_int_pair(16, 16, 16, inputs.F16, 11)
     a, b = G.decode_numpy(A, G.F16), G.decode_numpy(B, G.F16)
     ref = [[sum(a[i][k] * b[k][j] for k in range(16)) for j in range(16)] for i in range(16)]
-    p = S.plan(16, 16, 16, policy, 8, 8, 4, 6)
-    assert np.array_equal(simulate.run_plan(p, a, b).astype(np.float64), np.array(ref))
+    for k_aligned in (False, True):
+        p = S.plan(16, 16, 16, policy, 8, 8, 4, 6, k_aligned=k_aligned)
+        assert np.array_equal(simulate.run_plan(p, a, b).astype(np.float64), np.array(ref))
 
 
 @settings(max_examples=60, deadline=None)
@@ -245,7 +303,7 @@ def test_executed_schedule_is_exact_on_integer_inputs(shape, blk, g, policy, see
     M, N, K = shape
     A, B = inputs.small_int_pair(M, N, K, inputs.BF16, seed)
     a, b = G.decode_numpy(A, G.BF16), G.decode_numpy(B, G.BF16)
-    p = S.plan(M, N, K, policy, *blk, g, order=seed % 2)
+    p = S.plan(M, N, K, policy, *blk, g, order=seed % 2, dp_first=seed % 3 == 0, k_aligned=seed % 5 < 2)
     assert np.array_equal(simulate.run_plan(p, a, b).astype(np.float64), a @ b)
 
 
