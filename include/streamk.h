@@ -93,11 +93,13 @@ typedef enum { SK_STREAMK_FIRST = 0, SK_DATA_PARALLEL_FIRST = 1 } sk_batch_order
  * K offsets that differ by their distance in the iteration space, and the operand
  * blocks that neighbouring tiles share are fetched at different times (the loss
  * of cache locality Sec. 5.3 remarks on).
- * K_ALIGNED (default; measured 10-45 % faster on compute-bound sizes): a range that ends inside a tile other than the one it starts in runs
- * that head piece (K-iterations from 0) first, then the tail of its first tile,
- * then its whole tiles; all workgroups then move through K at nearly the same
- * pace.  The workgroup holding a tile's last K-iteration - the one that finishes
- * last - owns the tile; the owner adds the partials in descending workgroup order.
+ * K_ALIGNED (default): a range that contains a tile boundary runs its whole
+ * tiles first, then the head of its last tile (K-iterations from 0), then the
+ * tail of its first tile; whole tiles and head pieces then start at K-iteration
+ * 0 together in all workgroups.  The workgroup holding a tile's last
+ * K-iteration owns the tile - that piece is the last of its Stream-K work, so
+ * it never waits while other work is pending - and adds the partials in
+ * descending workgroup order.
  * Which workgroup runs which iterations is the same under both. */
 typedef enum { SK_SEGMENTS_ASCENDING = 0, SK_SEGMENTS_K_ALIGNED = 1 } sk_segment_order;
 

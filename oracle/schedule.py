@@ -43,12 +43,14 @@ R6  The workgroup whose segment holds a tile's k-iteration 0 owns the tile; the
     owner adds them in ascending workgroup order (= ascending k).
 R7  k_aligned=True is an execution order the paper does not have; it answers the
     loss of cache locality that Sec. 5.3 remarks on.  Which workgroup runs which
-    iterations is Algorithm 1's, unchanged.  A workgroup whose range ends inside a
-    tile other than the one it starts in runs that last piece (k-iterations from 0)
-    first, then the rest of its range in ascending order, so all workgroups move
-    through k at about the same pace.  The owner of a split tile is then the
-    workgroup holding the tile's last k-iteration (it finishes last), and it adds
-    the partials of the others in descending workgroup order.
+    iterations is Algorithm 1's, unchanged.  A workgroup whose range contains a
+    tile boundary runs its whole tiles first, then the piece at the end of its
+    range (k-iterations from 0 of its last tile), then the piece at the start of
+    its range (the last k-iterations of its first tile); whole tiles and pieces
+    from k = 0 then start together in all workgroups.  The owner of a split tile
+    is the workgroup holding the tile's last k-iteration - its final piece of work,
+    so it waits for nobody - and it adds the partials of the others in descending
+    workgroup order.
 """
 from collections import namedtuple
 
@@ -124,9 +126,10 @@ def wg_sk_range(x, sk_iters, iters_per_wg):
 def wg_sk_segments(x, begin, end, iters_per_tile, k_aligned=False):
     """Algorithm 1, the outer loop over a workgroup's range: cut [begin, end) at tile boundaries.
 
-    k_aligned (reading R7) moves a partial piece that starts at k-iteration 0 of a
-    later tile to the front, and hands the OWNER role to the piece that reaches
-    the tile's last iteration instead of the one that holds its first."""
+    k_aligned (reading R7) reorders a range that contains a tile boundary into
+    whole tiles, piece from k-iteration 0, piece up to the last k-iteration, and
+    hands the OWNER role to the piece that reaches the tile's last iteration
+    instead of the one that holds its first."""
     segs = []
     it = begin
     while it < end:
@@ -143,8 +146,11 @@ def wg_sk_segments(x, begin, end, iters_per_tile, k_aligned=False):
             role = ROLE_OWNER if local_iter == 0 else ROLE_CONTRIB
         segs.append(Segment(x, tile, local_iter, local_iter_end, role))
         it = tile_iter_end
-    if k_aligned and len(segs) > 1 and segs[-1].k_end < iters_per_tile:
-        segs.insert(0, segs.pop())
+    if k_aligned and len(segs) > 1:
+        whole = [s for s in segs if s.role == ROLE_FULL]
+        from_zero = [s for s in segs if s.role != ROLE_FULL and s.k_begin == 0]     # at most the last one
+        to_end = [s for s in segs if s.role != ROLE_FULL and s.k_begin > 0]         # at most the first one
+        segs = whole + from_zero + to_end
     return segs
 
 

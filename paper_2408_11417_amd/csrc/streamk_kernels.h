@@ -776,32 +776,35 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     if (it > g.sk_iters) it = g.sk_iters;
     if (it_end > g.sk_iters) it_end = g.sk_iters;
     int dp_tile = g.sk_tiles + x;   // data-parallel tiles come after the Stream-K work
-    // k-aligned order: a share that ends inside a tile other than the one it starts in gives up that
-    // head piece (k from 0) to be run first; the rest - the tail of the first tile, then whole
-    // tiles - follows in ascending order.  Workgroups then walk through k at nearly the same pace
-    // whatever their offset in the iteration space, which keeps the operand blocks they share in L2.
-    int head_tile = 0, head_k_end = 0;
+    // k-aligned order: a share that contains a tile boundary is run as its whole tiles first, then
+    // the head piece of its last tile (k from 0), then the tail piece of its first tile.  Whole
+    // tiles and head pieces then start at k = 0 at multiples of a tile's duration in every workgroup,
+    // whatever its offset in the iteration space, which keeps the operand blocks that neighbouring
+    // tiles share in L2; and the tail piece, whose workgroup owns the tile, comes last, when the
+    // pieces before it in k have long been parked.
+    int next_b = it_end, next_e = it_end, last_b = it_end, last_e = it_end;     // the sub-ranges after [it, it_end)
     if (g.k_aligned && it < it_end) {
-        const int last_tile = (int)((uint32_t)(it_end - 1) / (uint32_t)g.ipt);
-        const int last_first = last_tile * g.ipt;
-        if (last_first > it && it_end < last_first + g.ipt) {
-            head_tile = last_tile; head_k_end = it_end - last_first; it_end = last_first;
+        const int first_full = (int)(((uint32_t)it + (uint32_t)g.ipt - 1) / (uint32_t)g.ipt) * g.ipt;
+        const int last_full = (int)((uint32_t)it_end / (uint32_t)g.ipt) * g.ipt;
+        if (first_full <= last_full) {
+            next_b = last_full; next_e = it_end;     // head piece (may be empty)
+            last_b = it; last_e = first_full;        // tail piece (may be empty)
+            it = first_full; it_end = last_full;     // whole tiles (may be none)
         }
     }
 
     while (true) {
+        if (it >= it_end) { it = next_b; it_end = next_e; next_b = last_b; next_e = last_e; last_b = last_e; }
+        if (it >= it_end) { it = next_b; it_end = next_e; next_b = last_b; next_e = last_e; last_b = last_e; }
         int tile, k_begin, k_end;
-        const bool dp_now = dp_tile < g.tiles && (g.dp_first || (head_k_end == 0 && it >= it_end));
-        if (!dp_now && head_k_end > 0) {
-            tile = head_tile; k_begin = 0; k_end = head_k_end;
-            head_k_end = 0;
-        } else if (!dp_now && it < it_end) {     // Algorithm 1: cut the share at tile boundaries
+        const bool dp_now = dp_tile < g.tiles && (g.dp_first || it >= it_end);
+        if (!dp_now && it < it_end) {            // Algorithm 1: cut the share at tile boundaries
             tile = (int)((uint32_t)it / (uint32_t)g.ipt);
             const int tile_first = tile * g.ipt;
             k_begin = it - tile_first;
             const int stop = it_end < tile_first + g.ipt ? it_end : tile_first + g.ipt;
             k_end = stop - tile_first;
-            it = tile_first + g.ipt;
+            it = stop;
         } else if (dp_now) {
             tile = dp_tile; k_begin = 0; k_end = g.ipt;
             dp_tile += g.grid;

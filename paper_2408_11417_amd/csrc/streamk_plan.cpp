@@ -39,29 +39,32 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
         const bool contributor = k_aligned ? s.k_end < ipt : s.k_begin > 0;
         return contributor ? SK_ROLE_CONTRIB : SK_ROLE_OWNER;
     };
+    // a range that contains a tile boundary runs, in the k-aligned order, its whole tiles, then the
+    // head piece of its last tile, then the tail piece of its first tile
+    int64_t sub[3][2] = {{it, end}, {end, end}, {end, end}};
     if (k_aligned && it < end) {
-        // a range that ends inside another tile than it starts in runs that head piece first
-        const int64_t last_tile = (end - 1) / ipt, last_first = last_tile * ipt;
-        if (last_first > it && end < last_first + ipt) {
-            sk_segment s{x, (int32_t)last_tile, 0, (int32_t)(end - last_first), 0};
-            s.role = role_of(s);
-            if (out) out->push_back(s);
-            end = last_first;
+        const int64_t first_full = ceil_div(it, ipt) * ipt, last_full = end / ipt * ipt;
+        if (first_full <= last_full) {
+            sub[0][0] = first_full; sub[0][1] = last_full;
+            sub[1][0] = last_full;  sub[1][1] = end;
+            sub[2][0] = it;         sub[2][1] = first_full;
         }
     }
-    // Algorithm 1, outer loop: one segment per tile the range touches
-    while (it < end) {
-        const int64_t tile = it / ipt;
-        const int64_t tile_first = tile * ipt;
-        const int64_t stop = (end < tile_first + ipt) ? end : tile_first + ipt;
-        sk_segment s;
-        s.wg = x;
-        s.tile = (int32_t)tile;
-        s.k_begin = (int32_t)(it - tile_first);
-        s.k_end = (int32_t)(stop - tile_first);
-        s.role = role_of(s);
-        if (out) out->push_back(s);
-        it = tile_first + ipt;
+    for (const auto& r : sub) {
+        // Algorithm 1, outer loop: one segment per tile the range touches
+        for (int64_t i = r[0]; i < r[1];) {
+            const int64_t tile = i / ipt;
+            const int64_t tile_first = tile * ipt;
+            const int64_t stop = (r[1] < tile_first + ipt) ? r[1] : tile_first + ipt;
+            sk_segment s;
+            s.wg = x;
+            s.tile = (int32_t)tile;
+            s.k_begin = (int32_t)(i - tile_first);
+            s.k_end = (int32_t)(stop - tile_first);
+            s.role = role_of(s);
+            if (out) out->push_back(s);
+            i = stop;
+        }
     }
     // data-parallel tiles follow the Stream-K work (Sec. 4.1) - or precede it (Sec. 3.2's earlier hybrid)
     int32_t count = 0;
@@ -97,7 +100,7 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
         return SK_OK;
     }
     struct Cand { int bm, bn; double tflops; };
-    static const Cand cands[] = {{256, 256, 913.}, {256, 128, 738.}, {128, 128, 675.}, {64, 128, 527.}, {32, 128, 291.}, {16, 128, 41.}};
+    static const Cand cands[] = {{256, 256, 879.}, {256, 128, 816.}, {128, 128, 620.}, {64, 128, 439.}, {32, 128, 287.}, {16, 128, 46.}};
     const int bk = 64, grid = 256;
     const double ipt = (double)ceil_div(K, bk);
     double best_t = 0;
@@ -106,7 +109,7 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
         const Cand& c = cands[i];
         const double tiles = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
         const double t_iter = 2.0 * c.bm * c.bn * bk * grid / (c.tflops * 1e12) * 1e6;   // us per k-iteration
-        const double c_tile = 2.61 + c.bm * c.bn * 2 / 24.4e3;
+        const double c_tile = 1.73 + c.bm * c.bn * 2 / 58.6e3;
         const double waves = (double)((int64_t)((tiles + grid - 1) / grid));
         const double t_dp = waves * (ipt * t_iter + c_tile);
         const double ipw = (double)((int64_t)((tiles * ipt + grid - 1) / grid));
@@ -118,7 +121,7 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
             // partial tiles an owner (or a group leader) fetches one after the other: all of them up to
             // 16 workgroups per tile, beyond that the two-level reduction with groups of 8
             const double serial = split < 16 ? split : 8 + split / 8;
-            t_sk += 22.9 * (split < 16 ? 1 : 2) + serial * c.bm * c.bn * 4 / 37.8e3;
+            t_sk += 4.11 * (split < 16 ? 1 : 2) + serial * c.bm * c.bn * 4 / 35.1e3;
         }
         const double t = t_dp < t_sk ? t_dp : t_sk;
         if (best < 0 || t < best_t) { best = i; best_t = t; }

@@ -221,29 +221,33 @@ def test_k_aligned_order_keeps_the_work_and_moves_head_and_owner(shape, blk, g, 
     for x in range(g):
         sa = [s[:4] for s in a.segments if s.wg == x and s.tile < a.header["sk_tiles"]]
         sb = [s[:4] for s in b.segments if s.wg == x and s.tile < a.header["sk_tiles"]]
-        if len(sa) > 1 and sa[-1][3] < ipt:
-            assert sb == [sa[-1]] + sa[:-1]                               # the head piece moved to the front
-            assert sb[0][2] == 0
+        if len(sa) > 1:
+            whole = [s for s in sa if s[2] == 0 and s[3] == ipt]
+            head = [sa[-1]] if sa[-1][3] < ipt else []                     # the range's last piece, from k = 0
+            tail = [sa[0]] if sa[0][2] > 0 else []                         # the range's first piece, up to k = ipt
+            assert sb == whole + head + tail and len(sb) == len(sa)
+            # pace: every piece but the tail starts at k = 0 after a whole number of tiles
+            t = 0
+            for s in sb[:len(sb) - len(tail)]:
+                assert s[2] == 0 and t % ipt == 0
+                t += s[3] - s[2]
         else:
             assert sb == sa
-        # pace: a workgroup with a head and a tail piece walks k upwards with one jump of ipt - (its two pieces' length)
-        if len(sb) >= 2 and sb[0][3] < ipt and sb[1][2] > 0 and sb[0][1] != sb[1][1]:
-            assert sb[1][2] - sb[0][3] == ipt - ((sb[0][3] - sb[0][2]) + (sb[1][3] - sb[1][2]))
 
 
 def test_k_aligned_worked_example():
     # 5 tiles of 8 iterations over 4 workgroups, all Stream-K: 10 iterations each.
-    #   wg0: tile0 [0,8) whole, tile1 [0,2)        -> head first: tile1 [0,2) CONTRIB, tile0 FULL
-    #   wg1: tile1 [2,8), tile2 [0,4)              -> tile2 [0,4) CONTRIB, tile1 [2,8) OWNER
+    #   wg0: tile0 [0,8) whole, tile1 [0,2)        -> whole tile first: tile0 FULL, tile1 [0,2) CONTRIB
+    #   wg1: tile1 [2,8), tile2 [0,4)              -> head first: tile2 [0,4) CONTRIB, tile1 [2,8) OWNER
     #   wg2: tile2 [4,8), tile3 [0,6)              -> tile3 [0,6) CONTRIB, tile2 [4,8) OWNER
-    #   wg3: tile3 [6,8), tile4 [0,8) whole        -> tile3 [6,8) OWNER, tile4 FULL
+    #   wg3: tile3 [6,8), tile4 [0,8) whole        -> tile4 FULL, tile3 [6,8) OWNER
     p = S.plan(40, 8, 64, S.POLICY_ALL_SK, 8, 8, 8, 4, k_aligned=True)
     C, O, F = S.ROLE_CONTRIB, S.ROLE_OWNER, S.ROLE_FULL
     assert [tuple(s) for s in p.segments] == [
-        (0, 1, 0, 2, C), (0, 0, 0, 8, F),
+        (0, 0, 0, 8, F), (0, 1, 0, 2, C),
         (1, 2, 0, 4, C), (1, 1, 2, 8, O),
         (2, 3, 0, 6, C), (2, 2, 4, 8, O),
-        (3, 3, 6, 8, O), (3, 4, 0, 8, F)]
+        (3, 4, 0, 8, F), (3, 3, 6, 8, O)]
     q = S.plan(40, 8, 64, S.POLICY_ALL_SK, 8, 8, 8, 4)
     assert [tuple(s) for s in q.segments] == [
         (0, 0, 0, 8, F), (0, 1, 0, 2, O),
