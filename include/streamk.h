@@ -264,6 +264,16 @@ void sk_plan_destroy(sk_plan_t* plan);
  * it zero.  out_blk: host int32[3] = blk_m, blk_n, blk_k. */
 int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_blk);
 
+/* The dispatcher's cost model applied to this plan: a rough time estimate in
+ * microseconds (whole-tile waves, the evenly split Stream-K iterations, the
+ * exchange of partial tiles), from constants fitted on MI355X.  Meant for ranking
+ * the policies of one problem when no tuning record knows it (the selector's
+ * fall-back when the Bloom filters of Sec. 4.2 return no candidate), not for
+ * predicting times.  microseconds: host double.
+ * Errors: INVALID_ARG (NULL), UNSUPPORTED (fp8 inputs, or a tile shape the model
+ * has no constants for: anything but the six 16-bit shapes sk_default_tile picks from). */
+int sk_plan_estimate_us(const sk_plan_t* plan, double* microseconds);
+
 /* ---- Bloom-filter policy selector (Sec. 4.2) --------------------------------
  * One filter per policy.  A record says which policies are winners for a
  * problem size; the size is inserted into the filter of each of them.  A query

@@ -35,7 +35,7 @@ SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
            "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
-           "sk_plan_destroy", "sk_default_tile", "bloom_build", "bloom_insert", "bloom_query",
+           "sk_plan_destroy", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
 
@@ -85,6 +85,7 @@ _lib.sk_plan_set_spin_limit.argtypes = [_vp, ctypes.c_uint32]
 _lib.sk_plan_set_fixup.argtypes = [_vp, _int]
 _lib.sk_plan_set_batch_order.argtypes = [_vp, _int]
 _lib.sk_plan_set_segment_order.argtypes = [_vp, _int]
+_lib.sk_plan_estimate_us.argtypes = [_vp, ctypes.POINTER(ctypes.c_double)]
 _lib.sk_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sk_plan_check.argtypes = [_vp, _vp]
 _lib.sk_plan_destroy.argtypes = [_vp]
@@ -181,6 +182,12 @@ def sk_plan_set_fixup(plan, fixup):
 
 def sk_plan_set_batch_order(plan, batch_order):
     _check(_lib.sk_plan_set_batch_order(plan, batch_order), "sk_plan_set_batch_order")
+
+
+def sk_plan_estimate_us(plan):
+    us = ctypes.c_double()
+    _check(_lib.sk_plan_estimate_us(plan, ctypes.byref(us)), "sk_plan_estimate_us")
+    return us.value
 
 
 def sk_plan_set_segment_order(plan, segment_order):

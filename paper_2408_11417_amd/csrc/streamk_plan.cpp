@@ -82,34 +82,73 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
     }
 }
 
+// Cost model shared by the tile dispatcher and sk_plan_estimate_us.  The constants (sustained
+// TFLOP/s of each 16-bit kernel with the grid full, microseconds to drain / store a tile and to
+// park or fetch a partial) were fitted to timings of every tile shape on 500 seeded problem sizes
+// plus 12 large skinny ones on MI355X (fit_tile_model.py; the fit optimises the dispatcher's pick,
+// not the predicted times, so the constants need not be physical).
+struct TileCost { int bm, bn; double tflops; };
+const TileCost tile_costs[] = {{256, 256, 879.}, {256, 128, 816.}, {128, 128, 620.}, {64, 128, 439.}, {32, 128, 287.}, {16, 128, 46.}};
+constexpr int MODEL_BK = 64, MODEL_GRID = 256;
+double model_iter_us(const TileCost& c, int bk) {          // one k-iteration of every workgroup of a full grid
+    return 2.0 * c.bm * c.bn * bk * MODEL_GRID / (c.tflops * 1e12) * 1e6;
+}
+double model_tile_us(const TileCost& c) { return 1.73 + c.bm * c.bn * 2 / 58.6e3; }
+// exchange of partial tiles when about `split` workgroups share a tile: the partials an owner (or a
+// group leader) fetches one after the other - all of them up to 16 workgroups per tile, beyond that
+// the two-level reduction with groups of 8 where the kernel has one (two_level)
+double model_exchange_us(const TileCost& c, double split, bool two_level) {
+    const bool tree = two_level && split >= 16;
+    const double serial = tree ? 8 + split / 8 : split;
+    return 4.11 * (tree ? 2 : 1) + serial * c.bm * c.bn * 4 / 35.1e3;
+}
+
 }  // namespace
+
+extern "C" int sk_plan_estimate_us(const sk_plan_t* plan, double* microseconds) {
+    if (!plan || !microseconds) return SK_ERR_INVALID_ARG;
+    const sk_plan_header& h = plan->h;
+    const TileCost* c = nullptr;
+    for (const TileCost& t : tile_costs)
+        if (t.bm == h.blk_m && t.bn == h.blk_n) c = &t;
+    if (!c || h.in_dtype == SK_FP8_E4M3) return SK_ERR_UNSUPPORTED;
+    // per-iteration time of a workgroup does not depend on how many workgroups the grid has
+    const double t_iter = model_iter_us(*c, h.blk_k), c_tile = model_tile_us(*c);
+    double t = h.dp_waves * (h.iters_per_tile * t_iter + c_tile);
+    if (h.sk_tiles > 0) {
+        const double sk_waves = (double)h.sk_tiles / h.grid;
+        t += h.iters_per_wg * t_iter + c_tile * (sk_waves > 1 ? sk_waves : 1.0);
+        if (plan->needs_fixup) {
+            double split = (double)h.iters_per_tile / h.iters_per_wg;     // workgroups per tile beyond the owner, about
+            if (split < 1) split = 1;
+            t += model_exchange_us(*c, split, !(c->bm == 256 && c->bn == 256));  // the 256 x 256 tile reduces in one level
+        }
+    }
+    *microseconds = t;
+    return SK_OK;
+}
 
 extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_blk) {
     if (!out_blk || M < 1 || N < 1 || K < 1 || !dtype_in_ok(in_dtype)) return SK_ERR_INVALID_ARG;
     // Dispatcher: a small cost model over the tile shapes that have a kernel.  For each shape it
     // estimates the time of the better of (a) whole tiles in waves over the grid and (b) the
     // iterations split evenly over the grid plus the cost of exchanging partial tiles, and keeps
-    // the cheapest.  The constants (sustained TFLOP/s of each kernel with the grid full, microseconds
-    // to drain / store a tile and to park or fetch a partial) were fitted to timings of every tile
-    // shape on 500 seeded problem sizes plus 12 large skinny ones on MI355X (fit_tile_model.py; the
-    // fit optimises the pick, not the predicted times, so the constants need not be physical): the
-    // model's choice is then within 10 % of the fastest tile shape on 94 % of them.
+    // the cheapest; the model's choice is within 10 % of the fastest tile shape on 95 % of the
+    // sizes it was fitted on.
     if (in_dtype == SK_FP8_E4M3) {   // two 8-bit tile shapes: the large one unless it leaves most of the grid idle
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
         out_blk[0] = t256 >= 96 ? 256 : 128; out_blk[1] = 256; out_blk[2] = 128;
         return SK_OK;
     }
-    struct Cand { int bm, bn; double tflops; };
-    static const Cand cands[] = {{256, 256, 879.}, {256, 128, 816.}, {128, 128, 620.}, {64, 128, 439.}, {32, 128, 287.}, {16, 128, 46.}};
-    const int bk = 64, grid = 256;
+    const TileCost* cands = tile_costs;
+    const int bk = MODEL_BK, grid = MODEL_GRID;
     const double ipt = (double)ceil_div(K, bk);
     double best_t = 0;
     int best = -1;
-    for (int i = 0; i < (int)(sizeof cands / sizeof cands[0]); i++) {
-        const Cand& c = cands[i];
+    for (int i = 0; i < (int)(sizeof tile_costs / sizeof tile_costs[0]); i++) {
+        const TileCost& c = cands[i];
         const double tiles = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
-        const double t_iter = 2.0 * c.bm * c.bn * bk * grid / (c.tflops * 1e12) * 1e6;   // us per k-iteration
-        const double c_tile = 1.73 + c.bm * c.bn * 2 / 58.6e3;
+        const double t_iter = model_iter_us(c, bk), c_tile = model_tile_us(c);
         const double waves = (double)((int64_t)((tiles + grid - 1) / grid));
         const double t_dp = waves * (ipt * t_iter + c_tile);
         const double ipw = (double)((int64_t)((tiles * ipt + grid - 1) / grid));
@@ -117,12 +156,7 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
         if (split > ipt) split = ipt;
         if (split < 1) split = 1;
         double t_sk = ipw * t_iter + c_tile * (tiles > grid ? tiles / grid : 1.0);
-        if (((int64_t)tiles % grid) != 0) {
-            // partial tiles an owner (or a group leader) fetches one after the other: all of them up to
-            // 16 workgroups per tile, beyond that the two-level reduction with groups of 8
-            const double serial = split < 16 ? split : 8 + split / 8;
-            t_sk += 4.11 * (split < 16 ? 1 : 2) + serial * c.bm * c.bn * 4 / 35.1e3;
-        }
+        if (((int64_t)tiles % grid) != 0) t_sk += model_exchange_us(c, split, true);
         const double t = t_dp < t_sk ? t_dp : t_sk;
         if (best < 0 || t < best_t) { best = i; best_t = t; }
     }
@@ -173,9 +207,9 @@ extern "C" int sk_plan(int64_t M, int64_t N, int64_t K, int policy, const sk_con
         sk_tiles = tiles % grid + (int64_t)(b - 1) * grid;
         if (sk_tiles > tiles) sk_tiles = tiles;
     }
-    // Default tile order: workgroups of a pure Stream-K schedule sit at different k offsets of
-    // neighbouring tiles, where the row-major order measured faster; schedules with whole-tile
-    // (data-parallel) work gain from the compact blocks of the grouped order.
+    // Default tile order: schedules with whole-tile (data-parallel) work gain from the compact
+    // blocks of the grouped order; for a pure Stream-K schedule the two orders measure within a few
+    // per cent of each other and the plain one is kept.
     if (order < 0) order = (sk_tiles == tiles) ? SK_ORDER_ROW_MAJOR : SK_ORDER_GROUPED;
     h.tile_order = order;
     h.fixup = SK_FIXUP_FLAGS;

@@ -37,13 +37,25 @@ def shape_key(M, N, K, tile=None, grid=256, in_dtype=sk.SK_BF16):
         sk.sk_plan_destroy(plan)
 
 
-def fallback_policy(tiles, grid=256):
-    """Used when no filter knows the key: data-parallel if its waves of tiles keep at least 60 % of
-    the grid busy on average, otherwise one Stream-K batch over the remainder wave.  (The 60 %
-    was chosen on the build split of the sweep alone, scoring every build size as if it had fallen
-    through: mean selected / best 0.965 against 0.935 for "Stream-K whenever the last wave is ragged".)"""
-    waves = -(-tiles // grid)
-    return sk.SK_POLICY_DP if tiles * 10 >= waves * grid * 6 else sk.SK_POLICY_SK1_DP
+def model_estimates(M, N, K, tile, grid=256, dtype=sk.SK_BF16):
+    """The library's cost model (sk_plan_estimate_us, the tile dispatcher's model) for the seven policies."""
+    est = []
+    for p in range(N_POL):
+        plan = sk.sk_plan(M, N, K, p, tuple(tile), grid, dtype, dtype)
+        try:
+            est.append(sk.sk_plan_estimate_us(plan))
+        finally:
+            sk.sk_plan_destroy(plan)
+    return est
+
+
+def fallback_policy(M, N, K, tile, grid=256, dtype=sk.SK_BF16):
+    """Used when no filter knows the key: the policy the cost model ranks first; ties go to the
+    lower policy number.  Scoring every size of the sweep's build split as if it had fallen through,
+    the pick reaches 90 % of the best of seven on 98 % of them (mean 0.987); the earlier rule -
+    data-parallel if its waves keep 60 % of the grid busy, else one Stream-K batch - 89 % (mean 0.972)."""
+    est = model_estimates(M, N, K, tile, grid, dtype)
+    return est.index(min(est))
 
 
 class PolicySelector:
@@ -72,15 +84,19 @@ class PolicySelector:
 
     def select(self, r, times_ns=None):
         """(policy, candidate mask, used_fallback).  With times: the fastest candidate (the profiler
-        ran only the candidates); without: the candidate with most wins in the build set."""
+        ran only the candidates); without: the candidate the cost model ranks first (ties: the one
+        with most wins in the build set)."""
         mask = self.candidates(r)
         cands = [p for p in range(N_POL) if (mask >> p) & 1]
         fell_back = not cands
         if fell_back:
-            cands = [fallback_policy(r["tiles"], self.grid)]
+            cands = [fallback_policy(r["M"], r["N"], r["K"], r["tile"], self.grid)]
         if times_ns is not None:
             return min(cands, key=lambda p: times_ns[p]), mask, fell_back
-        return max(cands, key=lambda p: (self.wins[p], -p)), mask, fell_back
+        if len(cands) == 1:
+            return cands[0], mask, fell_back
+        est = model_estimates(r["M"], r["N"], r["K"], r["tile"], self.grid)
+        return min(cands, key=lambda p: (est[p], -self.wins[p], p)), mask, fell_back
 
     def close(self):
         sk.bloom_destroy(self.bloom)

@@ -231,3 +231,34 @@ def test_bloom_insert_after_build_and_errors():
     sk.bloom_destroy(b)
     with pytest.raises(sk.StreamKError):
         sk.bloom_build([], 100, 7, 7)                             # not a multiple of 64
+
+
+def test_plan_estimate_properties():
+    def est(M, N, K, policy, blk, grid=256, dtype=sk.SK_BF16):
+        p = sk.sk_plan(M, N, K, policy, blk, grid, dtype, sk.SK_BF16)
+        try:
+            return sk.sk_plan_estimate_us(p)
+        finally:
+            sk.sk_plan_destroy(p)
+    blk = (256, 256, 64)
+    one = est(4096, 4096, 4096, sk.SK_POLICY_DP, blk)                 # 256 tiles: one wave
+    two = est(8192, 4096, 4096, sk.SK_POLICY_DP, blk)                 # 512 tiles: two waves
+    assert one > 0 and abs(two - 2 * one) < 1e-9 * two
+    for policy in range(1, 7):                                       # whole waves: every policy is the same schedule
+        assert abs(est(8192, 4096, 4096, policy, blk) - two) < 1e-6 * two
+    # 257 tiles: the second, almost empty wave costs the data-parallel policy a whole tile time; a
+    # Stream-K batch over the 257 tiles (SK2_DP here) costs one iteration more per workgroup plus an exchange
+    dp = est(4096 + 256, 4096, 4096, sk.SK_POLICY_DP, (256, 256, 64))   # 17 x 16 = 272 tiles
+    sk2 = est(4096 + 256, 4096, 4096, sk.SK_POLICY_SK2_DP, (256, 256, 64))
+    assert dp > 1.9 * one and one < sk2 < 1.3 * one
+    # longer K costs more, bigger tiles cost more per tile
+    assert est(4096, 4096, 8192, 0, blk) > one and est(4096, 4096, 4096, 0, (128, 128, 64)) > 0
+    p = sk.sk_plan(4096, 4096, 4096, 0, (256, 256, 128), 256, sk.SK_FP8_E4M3, sk.SK_BF16)
+    us = ctypes.c_double()
+    lib = sk.binding._lib
+    assert lib.sk_plan_estimate_us(p, ctypes.byref(us)) == sk.SK_ERR_UNSUPPORTED
+    assert lib.sk_plan_estimate_us(p, None) == sk.SK_ERR_INVALID_ARG and lib.sk_plan_estimate_us(None, ctypes.byref(us)) == sk.SK_ERR_INVALID_ARG
+    sk.sk_plan_destroy(p)
+    p = sk.sk_plan(512, 512, 512, 0, (128, 128, 32), 256, sk.SK_F16, sk.SK_F16)   # blk_k = 32: the per-iteration time scales with blk_k
+    assert sk.sk_plan_estimate_us(p) > 0
+    sk.sk_plan_destroy(p)

@@ -54,9 +54,17 @@ def test_no_false_negatives_and_selection_rules():
         ps, _, _ = sel.select(r)
         assert (mask >> ps) & 1
     sel.close()
-    assert selector.fallback_policy(512) == sk.SK_POLICY_DP and selector.fallback_policy(495) == sk.SK_POLICY_DP
-    assert selector.fallback_policy(290) == sk.SK_POLICY_SK1_DP and selector.fallback_policy(100) == sk.SK_POLICY_SK1_DP
-    assert selector.fallback_policy(154) == sk.SK_POLICY_DP and selector.fallback_policy(153) == sk.SK_POLICY_SK1_DP
+
+
+def test_fallback_follows_the_cost_model():
+    # whole waves of tiles: nothing to gain from splitting -> data-parallel
+    assert selector.fallback_policy(4096, 4096, 4096, (256, 256, 64)) == sk.SK_POLICY_DP
+    # four tiles with 128 iterations each on 256 workgroups -> split them
+    assert selector.fallback_policy(64, 512, 8192, (32, 128, 64)) == sk.SK_POLICY_SK1_DP
+    # 265 tiles of 11 iterations: splitting 9 leftover tiles 28 ways costs more than it saves
+    assert selector.fallback_policy(13520, 560, 688, (256, 128, 64)) in (sk.SK_POLICY_DP, sk.SK_POLICY_SK2_DP)
+    # 289 tiles (1.13 waves) with 128 iterations: one or two Stream-K batches, not a second mostly empty wave
+    assert selector.fallback_policy(4352, 4352, 8192, (256, 256, 64)) in (sk.SK_POLICY_SK1_DP, sk.SK_POLICY_SK2_DP)
 
 
 def test_exact_filters_equal_oracle_filters_and_batch_query():
