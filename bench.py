@@ -17,9 +17,10 @@ import time
 
 import numpy as np
 
-# HBM bytes per launch of the data-parallel policy on the default workload, from rocprofv3
+# HBM bytes per launch of each policy on the default workload (k-aligned segment order), from rocprofv3
 # FETCH_SIZE / WRITE_SIZE scaled by a plain-copy calibration (profiles/streamk_gemm_kernel_cfg2_bf16_3840x4224x4096.txt)
-MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.3e6 + 32.8e6}
+MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.3e6 + 32.7e6, ("cfg2", "SK1_DP"): 413.3e6 + 64.0e6}
+MEASURED_TRAFFIC_BYTES.update({("cfg2", p): 402.1e6 + 64.3e6 for p in ("SK2_DP", "SK3_DP", "SK4_DP", "SK5_DP", "ALL_SK")})
 PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "e4m3": 5033.2}    # dense MFMA peak of MI355X
 
 
@@ -53,6 +54,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--policy", type=int, default=-1, help="skip tuning and run this policy only")
+    ap.add_argument("--ascending", action="store_true",
+                    help="Algorithm 1's order of a workgroup's Stream-K pieces instead of the library's k-aligned default (for A/B profiles)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -96,6 +99,8 @@ def main():
     plans, keep = {}, []
     for p in range(sk.SK_NUM_POLICIES):
         plan = sk.sk_plan(M, N, K, p, c["blk"], c["grid"], dt, c["out_dtype"])
+        if args.ascending:
+            sk.sk_plan_set_segment_order(plan, sk.SK_SEGMENTS_ASCENDING)
         nbytes = sk.sk_workspace_bytes(plan)
         ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
         sk.sk_plan_set_workspace(plan, (ws.data_ptr() + 255) // 256 * 256, nbytes)
@@ -109,21 +114,27 @@ def main():
         sk.sk_gemm(a.data_ptr(), b.data_ptr(), d.data_ptr(), (plan_set or plans)[p], stream)
 
     def time_policy(p, warm, timed, plan_set=None):
+        """ms per launch: `timed` launches back to back between one pair of events, as the timed
+        region below and the sweep run them (event pairs around every launch would add the launch
+        gap to each)."""
         for _ in range(warm):
             launch(p, plan_set)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(timed)]
-        for e0, e1 in evs:
-            e0.record()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(timed):
             launch(p, plan_set)
-            e1.record()
+        e1.record()
         torch.cuda.synchronize()
-        return float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))   # ms per launch
+        return e0.elapsed_time(e1) / timed
 
-    # ---- tuning pass (untimed): all seven policies, then the Bloom filters from the winners
+    # ---- tuning pass (untimed): all seven policies, then the Bloom filters from the winners.
+    # Two rounds over the policies, the faster of the two kept: the first policies timed in a fresh
+    # process otherwise run while the clocks are still settling and look slower than they are.
     if args.policy >= 0:
         t_pol = {args.policy: time_policy(args.policy, 10, 10)}
     else:
-        t_pol = {p: time_policy(p, 50, 50) for p in range(sk.SK_NUM_POLICIES)}
+        first = {p: time_policy(p, 50, 50) for p in range(sk.SK_NUM_POLICIES)}
+        t_pol = {p: min(first[p], time_policy(p, 50, 50)) for p in range(sk.SK_NUM_POLICIES)}
     best = min(t_pol.values())
     mask = sum(1 << p for p, t in t_pol.items() if t <= 1.2 * best)
     bloom = sk.bloom_build([(M, N, K, mask)])
@@ -195,10 +206,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": c["label"], "M": M, "N": N, "K": K,
                    "tile": [info["blk_m"], info["blk_n"], info["blk_k"]], "grid": info["grid"]},
-        "roofline": dict(roofline, traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, sk.POLICY_NAMES[sel])),
+        "roofline": dict(roofline, traffic=None if args.ascending else MEASURED_TRAFFIC_BYTES.get((args.workload, sk.POLICY_NAMES[sel])),
                          algorithmic_bytes=alg_bytes, kernel="streamk_gemm_kernel", kernel_ms=round(kernel_ms, 5),
                          step_event_ms=round(step_ms, 5)),
         "selected_policy": sk.POLICY_NAMES[sel],
+        "segment_order": "ascending" if args.ascending else "k_aligned",
         "selected_over_best": round(best / t_pol[sel], 4),
         "policies_tflops": {sk.POLICY_NAMES[p]: round(flops / (t * 1e-3) / 1e12, 2) for p, t in t_pol.items()},
         "bloom_candidates": [sk.POLICY_NAMES[p] for p in t_pol if (mask >> p) & 1],
