@@ -115,7 +115,8 @@ typedef enum { SK_ORDER_ROW_MAJOR = 0, SK_ORDER_GROUPED = 1 } sk_tile_order;
 /* Tile shape, grid and types.  A zero field means "library default": the tile
  * is then chosen from (M, N, K), grid = 256 (one workgroup per compute unit),
  * in_dtype = SK_BF16, out_dtype = in_dtype (SK_BF16 for fp8 inputs),
- * tile_order = SK_ORDER_ROW_MAJOR when every tile is in the Stream-K region, else SK_ORDER_GROUPED. */
+ * tile_order = whichever of the two orders makes the tiles that one XCD's workgroups hold at the
+ * same time span fewer operand rows and columns (see sk_tile_order). */
 typedef struct {
     int32_t blk_m, blk_n, blk_k;
     int32_t grid;

@@ -121,6 +121,17 @@ def sweep_shapes(n=500, seed=4, lo=64, hi=16384):
     return [tuple(int(v) for v in row) for row in dims]
 
 
+def paper_suite(n=923, seed=5):
+    """A suite shaped like the paper's (Sec. 5.1): dimensions in powers of two, M from 1 to 8192, N from
+    64 to 8192, K from 16 to 65536.  That grid has 14 x 8 x 13 = 1456 sizes; the paper used 923 of
+    them and does not list which, so this is a seeded sample of n of them, in random order (the
+    first 80 % serve as build split, the rest are held out)."""
+    grid = [(1 << m, 1 << nn, 1 << k) for m in range(0, 14) for nn in range(6, 14) for k in range(4, 17)]
+    rng = np.random.default_rng(seed)
+    pick = rng.permutation(len(grid))[:n]
+    return [grid[i] for i in pick]
+
+
 def sample_rows(M, n, seed):
     """n distinct seeded row indices of an M-row matrix (always including first and last)."""
     rng = np.random.default_rng(seed)

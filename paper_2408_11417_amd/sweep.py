@@ -35,7 +35,7 @@ def time_policy(sk, torch, plan, sets, stream, est_ms):
     return e0.elapsed_time(e1) / reps, reps
 
 
-def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False):
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False, tile_order=None):
     import torch
     import paper_2408_11417_amd as sk
 
@@ -69,7 +69,7 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
     for idx, (M, N, K) in enumerate(shapes):
         plans, infos = [], []
         for p in range(sk.SK_NUM_POLICIES):
-            plan = sk.sk_plan(M, N, K, p, tile, 256, dtype_code, dtype_code)
+            plan = sk.sk_plan(M, N, K, p, tile, 256, dtype_code, dtype_code, tile_order)
             sk.sk_plan_set_fixup(plan, fixup)
             if dp_first:
                 sk.sk_plan_set_batch_order(plan, sk.SK_DATA_PARALLEL_FIRST)
@@ -122,7 +122,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
             with open(out_path, "w") as f:
                 json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256,
                            "fixup": "atomic" if fixup else "flags", "dp_first": bool(dp_first),
-                           "segment_order": "ascending" if ascending else "k_aligned", "records": records}, f)
+                           "segment_order": "ascending" if ascending else "k_aligned",
+                           "tile_order": {None: "default", 0: "row_major", 1: "grouped"}[tile_order], "records": records}, f)
     return records
 
 
@@ -137,19 +138,26 @@ def main():
                     help="append the skinny family (M in 16..128, N = K in 4096, 8192; N = 16384, K = 4096) to the shapes")
     ap.add_argument("--dp-first", action="store_true",
                     help="data-parallel batches before the Stream-K work (the earlier hybrid of Sec. 3.2)")
+    ap.add_argument("--suite", choices=("random", "paper"), default="random",
+                    help="random: log-uniform sizes (inputs.sweep_shapes); paper: a seeded sample of the power-of-two grid "
+                         "of Sec. 5.1 (inputs.paper_suite)")
+    ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16")
+    ap.add_argument("--tile-order", choices=("default", "row_major", "grouped"), default="default",
+                    help="tile index -> tile grid position for every plan (default: the library's choice per schedule)")
     ap.add_argument("--ascending", action="store_true",
                     help="Algorithm 1's order of a workgroup's Stream-K pieces instead of the k-aligned default")
     ap.add_argument("--fixup", choices=("flags", "atomic"), default="flags",
                     help="how split tiles are combined (atomic = Algorithm 1's accumulation into C)")
     args = ap.parse_args()
     from paper_2408_11417_amd import inputs
-    shapes = inputs.sweep_shapes(args.shapes, args.seed)
+    shapes = inputs.paper_suite(args.shapes, args.seed) if args.suite == "paper" else inputs.sweep_shapes(args.shapes, args.seed)
     if args.first:
         shapes = shapes[:args.first]
     if args.skinny:
         shapes += [(M, N, K) for M in (16, 32, 64, 128) for N, K in ((8192, 8192), (4096, 4096), (16384, 4096))]
     tile = tuple(int(v) for v in args.tile.split(",")) if args.tile else None
-    run(shapes, args.out, fixup=1 if args.fixup == "atomic" else 0, tile=tile, dp_first=args.dp_first, ascending=args.ascending)
+    run(shapes, args.out, dtype_code=1 if args.dtype == "bf16" else 0, fixup=1 if args.fixup == "atomic" else 0, tile=tile, dp_first=args.dp_first, ascending=args.ascending,
+        tile_order={"default": None, "row_major": 0, "grouped": 1}[args.tile_order])
     return 0
 
 

@@ -272,6 +272,28 @@ def test_sweep_shapes_sampled_rows(index):
         _run_and_compare(A, B, inputs.BF16, policy, None, rows=rows, ref=ref)
 
 
+def _paper_suite_cases():
+    # power-of-two sizes of the paper-shaped suite, small enough for the fp64 oracle on sampled rows;
+    # the extremes of every dimension are among them
+    suite = inputs.paper_suite()
+    small = [s for s in suite if s[0] * s[1] * s[2] <= 1 << 31]
+    keep = small[::40]
+    for want in (min(small), max(small, key=lambda s: s[2]), min(small, key=lambda s: (s[2], -s[0])), max(small, key=lambda s: s[0])):
+        if want not in keep:
+            keep.append(want)
+    return keep
+
+
+@pytest.mark.parametrize("shape", _paper_suite_cases())
+def test_paper_suite_shapes_fp16_sampled_rows(shape):
+    M, N, K = shape
+    A, B = inputs.uniform_pair(M, N, K, inputs.F16, 200 + M % 97 + K % 89)
+    rows = inputs.sample_rows(M, min(M, 6), K)
+    ref = G.gemm_fp64(A, B, G.F16, rows=rows)
+    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(A, B, inputs.F16, policy, None, rows=rows, ref=ref)
+
+
 @pytest.mark.parametrize("blk,shape", [((32, 128, 64), (64, 208, 7872)), ((16, 128, 64), (48, 256, 6208)),
                                        ((64, 128, 64), (128, 128, 16448)), ((128, 128, 64), (128, 256, 8256)),
                                        ((32, 128, 64), (32, 1024, 4160)), (None, (112, 128, 3552))])

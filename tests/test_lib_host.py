@@ -82,9 +82,19 @@ def test_plan_defaults_and_errors():
     p = sk.sk_plan(8192, 8192, 8192, sk.SK_POLICY_DP)
     info = sk.sk_plan_info(p)
     assert (info["grid"], info["in_dtype"], info["out_dtype"]) == (256, sk.SK_BF16, sk.SK_BF16)
+    # 32 x 32 tiles: an XCD's 32 tiles are one tile row (1 + 32 operand blocks) or an 8 x 4 block (8 + 4)
     assert info["tile_order"] == sk.SK_ORDER_GROUPED
     q = sk.sk_plan(8192, 8192, 8192, sk.SK_POLICY_ALL_SK)
-    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_ROW_MAJOR      # pure Stream-K schedules default to row-major
+    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_GROUPED         # the choice does not depend on the policy
+    sk.sk_plan_destroy(q)
+    # one row of 64 tiles (cfg3): 8 tiles per XCD span 1 row and 8 columns either way -> the plain order
+    q = sk.sk_plan(16, 8192, 8192, sk.SK_POLICY_ALL_SK)
+    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_ROW_MAJOR
+    sk.sk_plan_destroy(q)
+    # 4 tile rows x 256 tile columns of 256 x 128 tiles: a row-major XCD chunk spans 1 x 32 blocks
+    # (256 + 32 * 128 operand rows and columns), a grouped one 4 x 8 (4 * 256 + 8 * 128)
+    q = sk.sk_plan(1024, 32768, 4096, sk.SK_POLICY_DP, (256, 128, 64))
+    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_GROUPED
     sk.sk_plan_destroy(q)
     with pytest.raises(sk.StreamKError):
         sk.sk_plan_tile_coords(p, info["tiles"])
