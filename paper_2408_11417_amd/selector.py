@@ -7,8 +7,9 @@ winner.  A query returns the candidate policies; the profiler then times only th
 timing is wanted - the candidate that won most often in the build set is taken.
 
     python -m paper_2408_11417_amd.selector --sweep sweep_bf16.json --split 400
+    python -m paper_2408_11417_amd.selector --tile-sweeps sweep_tile_*.json --split 400     (tile shape as a second parameter)
 
-prints, for tolerances 0 / 5 % / 20 %: false negatives on the build split, pruning rate, and on
+The first prints, for tolerances 0 / 5 % / 20 %: false negatives on the build split, pruning rate, and on
 the held-out split the ratio selected / best and the share of shapes at >= 90 % of the best.
 All filter work goes through the C library; nothing here needs a GPU.
 """
@@ -184,12 +185,120 @@ def sweep_statistics(records):
     return out
 
 
+# ---- tile shape as a second Bloom-filtered tuning parameter -----------------------------------
+# Sec. 4.2 closes with the remark that further tuning parameters can get filters of their own.  Here:
+# one filter per tile shape the dispatcher picks from; a size is inserted into the filters of the
+# tile shapes whose best policy is within a tolerance of the best (tile, policy) pair of that size.
+
+def size_class_key(M, N, K, octaves=(1, 1, 2)):
+    """Key for sizes that were never profiled: the size class ceil(log2 dim) of each dimension, in
+    units of `octaves` octaves (tile choice depends mostly on how many tiles M and N make, less on K)."""
+    return tuple(((int(d) - 1).bit_length() + o - 1) // o for d, o in zip((M, N, K), octaves))
+
+
+def tile_records(sweeps):
+    """sweeps: {tile: records of a sweep run with --tile}.  Returns per size (M, N, K) a dict
+    tile -> best time over the policies, in the order of the first sweep."""
+    tiles = list(sweeps)
+    out = []
+    for i, r in enumerate(sweeps[tiles[0]]):
+        size = (r["M"], r["N"], r["K"])
+        best = {}
+        for t in tiles:
+            q = sweeps[t][i]
+            assert (q["M"], q["N"], q["K"]) == size
+            best[t] = min(q["time_ns"])
+        out.append((size, best))
+    return out
+
+
+class TileSelector:
+    """One Bloom filter per tile shape.  mode 'exact' keys by (M, N, K); mode 'class' by size_class_key."""
+
+    def __init__(self, recs, tiles, tol=0.1, mode="class", octaves=(1, 1, 2)):
+        self.tiles, self.tol, self.mode, self.octaves = list(tiles), tol, mode, octaves
+        merged = {}
+        for size, best in recs:
+            key = self.key_of(size)
+            merged[key] = merged.get(key, 0) | winner_mask([best[t] for t in self.tiles], tol)
+        self.inserted = merged
+        self.bloom = sk.bloom_build([(k[0], k[1], k[2], m) for k, m in merged.items()], n_filters=len(self.tiles))
+
+    def key_of(self, size):
+        return tuple(size) if self.mode == "exact" else size_class_key(*size, self.octaves)
+
+    def candidates(self, size):
+        return sk.bloom_query(self.bloom, *self.key_of(size))
+
+    def select(self, size):
+        """(tile, candidate mask, used_fallback): among the candidate tile shapes the one the library's
+        cost model ranks first (under its best policy); among all tile shapes when no filter knows the key."""
+        mask = self.candidates(size)
+        cands = [t for i, t in enumerate(self.tiles) if (mask >> i) & 1]
+        if len(cands) == 1:
+            return cands[0], mask, False
+        return self.model_pick(size, cands or self.tiles), mask, not cands
+
+    @staticmethod
+    def model_pick(size, tiles):
+        return min(tiles, key=lambda t: min(model_estimates(*size, t)))
+
+    def close(self):
+        sk.bloom_destroy(self.bloom)
+
+
+def evaluate_tiles(recs, split, tol, mode, octaves=(1, 1, 2)):
+    build, held = recs[:split], recs[split:]
+    tiles = list(build[0][1])
+    sel = TileSelector(build, tiles, tol, mode, octaves)
+    out = {"tol": tol, "mode": mode, "octaves": list(octaves), "tiles": [list(t) for t in tiles],
+           "build_sizes": len(build), "held_out_sizes": len(held), "distinct_keys": len(sel.inserted)}
+    fn = kept = 0
+    for size, best in build:
+        want = winner_mask([best[t] for t in tiles], tol)
+        got = sel.candidates(size)
+        fn += bin(want & ~got).count("1")
+        kept += bin(got).count("1")
+    out["false_negatives"] = fn
+    out["pruning_rate_build"] = 1 - kept / (len(tiles) * len(build))
+    ratios, ratios_model, fallbacks, kept = [], [], 0, 0
+    for size, best in held:
+        tile, mask, fb = sel.select(size)
+        fallbacks += fb
+        kept += bin(mask).count("1") or 1
+        ratios.append(min(best.values()) / best[tuple(tile)])
+        ratios_model.append(min(best.values()) / best[sel.model_pick(size, tiles)])
+    n = max(len(held), 1)
+    out.update({"held_fallbacks": fallbacks, "held_pruning_rate": 1 - kept / (len(tiles) * n),
+                "held_mean_ratio": sum(ratios) / n, "held_min_ratio": min(ratios) if ratios else None,
+                "held_share_ge_0.9_of_best": sum(x >= 0.9 for x in ratios) / n,
+                "cost_model_alone_mean_ratio": sum(ratios_model) / n,
+                "cost_model_alone_share_ge_0.9": sum(x >= 0.9 for x in ratios_model) / n})
+    sel.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sweep", required=True)
+    ap.add_argument("--sweep", default="")
+    ap.add_argument("--tile-sweeps", nargs="*", default=[],
+                    help="sweep files made with --tile, one per tile shape: evaluate tile-shape filters instead of policy filters")
     ap.add_argument("--split", type=int, default=400)
     ap.add_argument("--out", default="")
     args = ap.parse_args()
+    if args.tile_sweeps:
+        sweeps = {}
+        for f in args.tile_sweeps:
+            recs = json.load(open(f))["records"]
+            sweeps[tuple(recs[0]["tile"])] = recs
+        recs = tile_records(sweeps)
+        report = {"tile_evaluations": [evaluate_tiles(recs, args.split, tol, mode)
+                                       for mode in ("exact", "class") for tol in (0.0, 0.05, 0.1, 0.2)]}
+        text = json.dumps(report, indent=1)
+        print(text)
+        if args.out:
+            open(args.out, "w").write(text)
+        return 0
     records = json.load(open(args.sweep))["records"]
     report = {"statistics": sweep_statistics(records), "evaluations": []}
     for mode in ("exact", "shape"):

@@ -98,3 +98,30 @@ def test_runner_up_margin_by_hand():
     rec = {"M": 64, "N": 64, "K": 64, "tiles": 4, "sk_tiles": [0, 4, 4, 4, 4, 4, 4], "time_ns": [100, 80, 80, 80, 80, 80, 80]}
     st = selector.sweep_statistics([rec])
     assert st["gain_over_runner_up"] == {"SK1_DP": {"sizes": 1, "median": 0.25, "p90": 0.25, "max": 0.25}}
+
+
+def test_tile_filters_no_false_negatives_and_fallback():
+    rng = random.Random(7)
+    tiles = [(256, 256, 64), (128, 128, 64), (32, 128, 64)]
+    recs = []
+    for _ in range(90):
+        size = tuple(16 * rng.randint(4, 512) for _ in range(3))
+        small = size[0] * size[1] < 512 * 512
+        recs.append((size, {tiles[0]: 9000 if small else 5000, tiles[1]: 7000 + rng.randint(0, 50),
+                            tiles[2]: 5000 if small else 9000}))
+    for mode in ("exact", "class"):
+        sel = selector.TileSelector(recs[:60], tiles, 0.1, mode)
+        for size, best in recs[:60]:
+            want = selector.winner_mask([best[t] for t in tiles], 0.1)
+            assert sel.candidates(size) & want == want                    # every inserted winner comes back
+            tile, mask, fb = sel.select(size)
+            assert not fb and tile in tiles and (mask >> tiles.index(tile)) & 1
+        sel.close()
+        rep = selector.evaluate_tiles(recs, 60, 0.1, mode)
+        assert rep["false_negatives"] == 0 and 0 < rep["held_mean_ratio"] <= 1
+        assert rep["held_fallbacks"] == (30 if mode == "exact" else rep["held_fallbacks"])
+    assert selector.size_class_key(64, 65, 4096) == (6, 7, 6) and selector.size_class_key(1, 2, 3, (1, 1, 1)) == (0, 1, 2)
+    # a size no filter knows falls back to the dispatcher's own tile
+    sel = selector.TileSelector(recs[:5], tiles, 0.0, "exact")
+    assert sel.select((4096, 4096, 4096)) == ((256, 256, 64), 0, True)     # 256 tiles of 256 x 256: one full wave
+    sel.close()
