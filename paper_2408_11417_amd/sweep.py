@@ -26,13 +26,21 @@ def time_policy(sk, torch, plan, sets, stream, est_ms):
     reps = 50 if est_ms <= 0.2 else max(5, int(20.0 / est_ms))
     for i in range(reps):
         sk.sk_gemm(*sets[i % len(sets)], plan, stream)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(reps):
-        sk.sk_gemm(*sets[i % len(sets)], plan, stream)
-    e1.record()
-    e1.synchronize()
-    return e0.elapsed_time(e1) / reps, reps
+
+    def timed():
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            sk.sk_gemm(*sets[i % len(sets)], plan, stream)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms = timed()
+    if ms > 1.5 * est_ms:
+        # far above the single launch timed beforehand: something else held the machine up; once more
+        ms = min(ms, timed())
+    return ms, reps
 
 
 def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False, tile_order=None):
@@ -56,8 +64,12 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
             out[i:i + m] = (torch.rand(m, device="cuda", generator=gen) * 2 - 1).to(tdt)
         return out
 
-    pa, pb = pool(max_a), pool(max_b)
-    pd = torch.empty(max_d, dtype=tdt, device="cuda")
+    # room for four copies of the largest operands, so that every size rotates over four sets
+    # (at least 4 x the operand bytes between two uses of the same set: more than the 256 MB
+    # memory-side cache holds for every operand above 64 MB, which is where that cache would matter)
+    slack = 4 * 256
+    pa, pb = pool(4 * max_a + slack), pool(4 * max_b + slack)
+    pd = torch.empty(4 * max_d + slack, dtype=tdt, device="cuda")
     pd2 = torch.empty(max_d, dtype=tdt, device="cuda")
     ws_bytes = 256 * 256 * 256 * 4 + (1 << 16)
     if fixup:                                  # the atomic fix-up keeps an fp32 image of D in the workspace
@@ -82,11 +94,10 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
         # policies whose Stream-K region covers the same number of tiles are the same schedule
         by_sched, times, reps_used = {}, [0.0] * 7, [0] * 7
         dA, dB, dD = pa.data_ptr(), pb.data_ptr(), pd.data_ptr()
-        # up to four operand sets carved out of the pools at 256-byte aligned offsets
-        copies = max(1, min(4, max_a // (M * K), max_b // (K * N), max_d // (M * N)))
+        # four operand sets carved out of the pools at 256-byte aligned offsets
+        copies = 4
         step = lambda n: (n * 2 + 255) // 256 * 256
-        if copies > 1 and (step(M * K) * copies > max_a * 2 or step(K * N) * copies > max_b * 2 or step(M * N) * copies > max_d * 2):
-            copies -= 1
+        assert step(M * K) * copies <= pa.numel() * 2 and step(K * N) * copies <= pb.numel() * 2 and step(M * N) * copies <= pd.numel() * 2
         sets = [(dA + c * step(M * K), dB + c * step(K * N), dD + c * step(M * N)) for c in range(copies)]
         for p in range(sk.SK_NUM_POLICIES):
             key = infos[p]["sk_tiles"]
