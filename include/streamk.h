@@ -70,8 +70,8 @@ typedef enum {
 
 /* How the partial results of a split tile are combined.
  * FLAGS (default): the workspace-and-flags exchange described at sk_role, the
- * alternative Sec. 5.3 names; the owner adds the partials in ascending workgroup
- * order, so D is bit-identical from run to run.
+ * alternative Sec. 5.3 names; the owner adds the partials in a fixed order
+ * (see sk_segment_order), so D is bit-identical from run to run.
  * ATOMIC: the accumulation step of Algorithm 1, as printed: every workgroup that holds only
  * part of a tile's K-iterations adds its accumulators into a zero-initialised
  * fp32 image of D with atomic adds, nobody waits for anybody.  The order of the
@@ -109,14 +109,17 @@ typedef enum { SK_SEGMENTS_ASCENDING = 0, SK_SEGMENTS_K_ALIGNED = 1 } sk_segment
  * mind: the grid is cut into bands of 8 tile rows; inside a band the index
  * walks down the band's rows, then one column to the right, so consecutive
  * indices (which run at the same time on neighbouring workgroups) share A
- * row-blocks and B column-blocks. */
+ * row-blocks and B column-blocks.  When sk_config leaves the order open the
+ * library takes, per plan, the order under which the tiles that one XCD's
+ * workgroups hold at the same time (an eighth of the first min(tiles, grid) tile
+ * indices) span fewer operand rows and columns: A row-blocks x blk_m + B
+ * column-blocks x blk_n. */
 typedef enum { SK_ORDER_ROW_MAJOR = 0, SK_ORDER_GROUPED = 1 } sk_tile_order;
 
 /* Tile shape, grid and types.  A zero field means "library default": the tile
  * is then chosen from (M, N, K), grid = 256 (one workgroup per compute unit),
  * in_dtype = SK_BF16, out_dtype = in_dtype (SK_BF16 for fp8 inputs),
- * tile_order = whichever of the two orders makes the tiles that one XCD's workgroups hold at the
- * same time span fewer operand rows and columns (see sk_tile_order). */
+ * tile_order = chosen per plan (see sk_tile_order). */
 typedef struct {
     int32_t blk_m, blk_n, blk_k;
     int32_t grid;
@@ -161,8 +164,8 @@ typedef struct {
 
 typedef struct sk_plan_t sk_plan_t;
 
-/* Build the schedule of one problem under one policy (Algorithm 1, lines 2-6;
- * Sec. 3.2; Sec. 4.1).  Host only, no device contact.  cfg may be NULL (all
+/* Build the schedule of one problem under one policy (Algorithm 1, up to the
+ * per-workgroup iteration range; Sec. 3.2; Sec. 4.1).  Host only, no device contact.  cfg may be NULL (all
  * defaults).  Any positive tile shape is accepted for planning; whether sk_gemm
  * can run it is reported in sk_plan_header.has_kernel.
  * Errors: INVALID_ARG (sizes < 1, unknown policy / dtype, totals beyond int32
@@ -176,8 +179,9 @@ int sk_plan_info(const sk_plan_t* plan, sk_plan_header* out);
 int sk_plan_ranges(const sk_plan_t* plan, sk_wg_range* out);
 
 /* Canonical expansion of the schedule: segments ordered by workgroup and, inside
- * a workgroup, in execution order (Stream-K segments, then data-parallel tiles,
- * Sec. 4.1; the other way round under SK_DATA_PARALLEL_FIRST).  out is host memory for `cap` entries (may be NULL when cap = 0);
+ * a workgroup, in execution order (Stream-K segments in the plan's segment
+ * order, then data-parallel tiles, Sec. 4.1; the other way round under
+ * SK_DATA_PARALLEL_FIRST).  out is host memory for `cap` entries (may be NULL when cap = 0);
  * *n receives the number of segments; INVALID_ARG if cap is too small (then *n
  * still receives the needed count). */
 int sk_plan_segments(const sk_plan_t* plan, sk_segment* out, size_t cap, size_t* n);

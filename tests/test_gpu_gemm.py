@@ -182,7 +182,7 @@ def test_config5_large_square_fp8_sampled_rows():
         _run_and_compare(c["A"], c["B"], inputs.E4M3, policy, None, 256, rows=rows, ref=ref)
 
 
-# ---- atomic-add fix-up (Algorithm 1, lines 14-18): same schedules, partial tiles added into a zeroed fp32 image
+# ---- atomic-add fix-up (the accumulation step of Algorithm 1): same schedules, partial tiles added into a zeroed fp32 image
 
 @pytest.mark.parametrize("blk", [t[:3] for t in TILES])
 def test_atomic_fixup_integer_inputs_bit_exact(blk):
