@@ -148,15 +148,21 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # the timed region: exactly `steps` steps, nothing else on the stream (no event records between
+    # the steps: each would put a marker and a few microseconds of gap between two launches)
     t0 = time.perf_counter()
-    for e0, e1 in evs:
-        e0.record()
+    for _ in range(args.steps):
         sel = step()
-        e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     assert sk.sk_plan_check(plans[sel], stream) == sk.SK_OK
+    # the same steps once more with an event pair around each, for the per-step figure
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
     # kernel time of the selected policy: the same number of launches back to back between one pair
     # of events on the launch stream (per-launch event pairs would add the launch gap, which matters
     # for the 30 us skinny kernels)

@@ -145,6 +145,13 @@ typedef struct {
     int32_t tile_order;                   /* sk_tile_order                                   */
     int32_t fixup, batch_order, segment_order;  /* sk_fixup, sk_batch_order, sk_segment_order: the
                                              defaults, or what the sk_plan_set_* calls chose */
+    int32_t xcd_remap;                    /* 1: the kernel renumbers the workgroups so that each of the 8 XCDs
+                                             runs grid/8 consecutive ones (neighbours in the schedule, which share
+                                             operand blocks, then share an L2); 0: hardware order, consecutive
+                                             workgroups on different XCDs - chosen when the tile grid is a single
+                                             row of tiles at most 64 rows high, where B is streamed once in narrow
+                                             column blocks and spreading neighbouring blocks over the XCDs
+                                             measured 8-10 % faster */
 } sk_plan_header;
 
 /* Work of one workgroup x: global Stream-K iterations [sk_iter_begin, sk_iter_end)

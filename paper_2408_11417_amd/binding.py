@@ -52,7 +52,8 @@ class sk_plan_header(ctypes.Structure):
                 ("total_iters", ctypes.c_int64), ("sk_tiles", ctypes.c_int32), ("dp_tiles", ctypes.c_int32),
                 ("sk_iters", ctypes.c_int64), ("iters_per_wg", ctypes.c_int32), ("dp_waves", ctypes.c_int32),
                 ("has_kernel", ctypes.c_int32), ("tile_order", ctypes.c_int32),
-                ("fixup", ctypes.c_int32), ("batch_order", ctypes.c_int32), ("segment_order", ctypes.c_int32)]
+                ("fixup", ctypes.c_int32), ("batch_order", ctypes.c_int32), ("segment_order", ctypes.c_int32),
+                ("xcd_remap", ctypes.c_int32)]
 
 
 class sk_wg_range(ctypes.Structure):

@@ -138,6 +138,7 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     g.out_dtype = h.out_dtype;
     g.dp_first = plan->dp_first;
     g.k_aligned = plan->k_aligned;
+    g.xcd_remap = h.xcd_remap;
     if (atomic) {
         // Algorithm 1's atomic accumulation needs C to start at zero: clear the image in-stream, accumulate, convert
         const size_t n = (size_t)h.M * (size_t)h.N;

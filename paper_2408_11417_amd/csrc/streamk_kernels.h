@@ -47,8 +47,10 @@ struct GemmArgs {
     uint32_t spin_limit;
     int out_dtype;
     int dp_first;          // 1: a workgroup runs its data-parallel tiles before its Stream-K iterations
-    int k_aligned;         // 1: a workgroup runs the head of its last Stream-K tile (k from 0) before the tail of its
-                           //    first one, and the workgroup holding a tile's last iteration reduces and stores it
+    int xcd_remap;         // 1: consecutive logical workgroup ids share an XCD (see logical_wg)
+    int k_aligned;         // 1: a workgroup runs the whole tiles of its Stream-K range first, then the head of its last
+                           //    tile (k from 0), then the tail of its first one, and the workgroup holding a tile's
+                           //    last iteration reduces and stores it
 };
 
 // ---- matrix-core wrappers ---------------------------------------------------------------------
@@ -195,9 +197,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 
 // Hardware workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous block of
 // logical workgroup ids so that neighbours in the schedule (which share tiles and A row-blocks)
-// share an L2.
-__device__ __forceinline__ int logical_wg(int hw, int grid) {
-    return (grid % 8 == 0) ? (hw % 8) * (grid / 8) + hw / 8 : hw;
+// share an L2.  Plans with a single row of low tiles keep the hardware order: their workgroups
+// only stream B, and neighbouring column blocks read from different XCDs reach a higher HBM rate.
+__device__ __forceinline__ int logical_wg(int hw, int grid, int remap) {
+    return (remap && grid % 8 == 0) ? (hw % 8) * (grid / 8) + hw / 8 : hw;
 }
 
 // 16 bytes whose address is only known to be a multiple of the element size (rows of a matrix whose
@@ -764,7 +767,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     typedef typename Mfma<C::DT, C::MF>::Acc Acc;
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / C::WN, wn = wave % C::WN;
-    const int x = logical_wg(blockIdx.x, g.grid);
+    const int x = logical_wg(blockIdx.x, g.grid, g.xcd_remap);
     // transposed accumulator blocks (vector stores) where D's rows are 16-byte aligned; the atomic
     // fix-up and the element-wise stores of unaligned problems want the lanes side by side in a row
     constexpr bool TR = ALIGNED && !ATOMIC;

@@ -87,10 +87,17 @@ def test_plan_defaults_and_errors():
     q = sk.sk_plan(8192, 8192, 8192, sk.SK_POLICY_ALL_SK)
     assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_GROUPED         # the choice does not depend on the policy
     sk.sk_plan_destroy(q)
-    # one row of 64 tiles (cfg3): 8 tiles per XCD span 1 row and 8 columns either way -> the plain order
+    # one row of 64 tiles (cfg3): 8 tiles per XCD span 1 row and 8 columns either way -> the plain order;
+    # a single row of low tiles keeps the hardware workgroup order, everything else is renumbered per XCD
     q = sk.sk_plan(16, 8192, 8192, sk.SK_POLICY_ALL_SK)
-    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_ROW_MAJOR
+    assert sk.sk_plan_info(q)["tile_order"] == sk.SK_ORDER_ROW_MAJOR and sk.sk_plan_info(q)["xcd_remap"] == 0
     sk.sk_plan_destroy(q)
+    assert info["xcd_remap"] == 1
+    for shape, blk, remap in (((128, 8192, 8192), (128, 128, 64), 1), ((128, 8192, 8192), (64, 128, 64), 1),
+                              ((64, 8192, 8192), (64, 128, 64), 0), ((8192, 128, 8192), (64, 128, 64), 1)):
+        q = sk.sk_plan(*shape, sk.SK_POLICY_ALL_SK, blk)
+        assert sk.sk_plan_info(q)["xcd_remap"] == remap
+        sk.sk_plan_destroy(q)
     # 4 tile rows x 256 tile columns of 256 x 128 tiles: a row-major XCD chunk spans 1 x 32 blocks
     # (256 + 32 * 128 operand rows and columns), a grouped one 4 x 8 (4 * 256 + 8 * 128)
     q = sk.sk_plan(1024, 32768, 4096, sk.SK_POLICY_DP, (256, 128, 64))
