@@ -279,3 +279,24 @@ def test_plan_estimate_properties():
     p = sk.sk_plan(512, 512, 512, 0, (128, 128, 32), 256, sk.SK_F16, sk.SK_F16)   # blk_k = 32: the per-iteration time scales with blk_k
     assert sk.sk_plan_estimate_us(p) > 0
     sk.sk_plan_destroy(p)
+
+
+def test_seeded_suites_are_reproducible_and_in_range():
+    from paper_2408_11417_amd import inputs
+    a, b = inputs.sweep_shapes(500, 4), inputs.sweep_shapes(500, 4)
+    assert a == b and len(a) == 500
+    assert all(64 <= d <= 16384 and d % 16 == 0 for s in a for d in s)
+    p = inputs.paper_suite()
+    assert p == inputs.paper_suite() and len(p) == 923 and len(set(p)) == 923
+    for M, N, K in p:                                     # powers of two inside the ranges of Sec. 5.1
+        assert all(d & (d - 1) == 0 for d in (M, N, K))
+        assert 1 <= M <= 8192 and 64 <= N <= 8192 and 16 <= K <= 65536
+    assert len(inputs.paper_suite(1456)) == 1456 == len(set(inputs.paper_suite(1456)))      # the whole grid
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "--gpus must be 1" in (res.stderr + res.stdout)
