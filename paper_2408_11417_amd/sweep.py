@@ -18,20 +18,34 @@ import time
 import numpy as np
 
 
-def time_policy(sk, torch, plan, sets, stream, est_ms):
+def time_policy(sk, torch, plan, sets, stream, est_ms, graph=False):
     """Mean milliseconds per launch; repetitions follow the paper's 50 + 50 protocol for kernels up
     to 0.2 ms and shrink to >= 5 + 5 (about 20 ms of timed work) for longer ones.  `sets`: (A, B, D)
     pointer triples the launches rotate over, so that operands smaller than the 256 MB memory-side
-    cache are not served from it launch after launch."""
+    cache are not served from it launch after launch.  graph=True captures the timed launches into a
+    HIP graph once and times a replay: kernels of a few microseconds are then not held up by the rate
+    at which the host can enqueue them."""
     reps = 50 if est_ms <= 0.2 else max(5, int(20.0 / est_ms))
     for i in range(reps):
         sk.sk_gemm(*sets[i % len(sets)], plan, stream)
+    replay = None
+    if graph:
+        replay = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(replay):
+            capture_stream = torch.cuda.current_stream().cuda_stream
+            for i in range(reps):
+                sk.sk_gemm(*sets[i % len(sets)], plan, capture_stream)
+        replay.replay()                                  # one untimed replay
+        torch.cuda.synchronize()
 
     def timed():
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for i in range(reps):
-            sk.sk_gemm(*sets[i % len(sets)], plan, stream)
+        if replay is not None:
+            replay.replay()
+        else:
+            for i in range(reps):
+                sk.sk_gemm(*sets[i % len(sets)], plan, stream)
         e1.record()
         e1.synchronize()
         return e0.elapsed_time(e1) / reps
@@ -43,7 +57,8 @@ def time_policy(sk, torch, plan, sets, stream, est_ms):
     return ms, reps
 
 
-def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False, tile_order=None):
+def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False, tile_order=None,
+        graph=False):
     import torch
     import paper_2408_11417_amd as sk
 
@@ -108,7 +123,7 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
                 sk.sk_gemm(dA, dB, dD, plans[p], stream)
                 e1.record()
                 e1.synchronize()
-                by_sched[key] = time_policy(sk, torch, plans[p], sets, stream, e0.elapsed_time(e1))
+                by_sched[key] = time_policy(sk, torch, plans[p], sets, stream, e0.elapsed_time(e1), graph)
             times[p], reps_used[p] = by_sched[key]
         rec = {"M": M, "N": N, "K": K, "tile": [infos[0]["blk_m"], infos[0]["blk_n"], infos[0]["blk_k"]],
                "tiles": infos[0]["tiles"], "iters_per_tile": infos[0]["iters_per_tile"],
@@ -134,7 +149,8 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
                 json.dump({"dtype": "bf16" if dtype_code == 1 else "f16", "grid": 256,
                            "fixup": "atomic" if fixup else "flags", "dp_first": bool(dp_first),
                            "segment_order": "ascending" if ascending else "k_aligned",
-                           "tile_order": {None: "default", 0: "row_major", 1: "grouped"}[tile_order], "records": records}, f)
+                           "tile_order": {None: "default", 0: "row_major", 1: "grouped"}[tile_order],
+                           "timing": "graph replay" if graph else "eager launches", "records": records}, f)
     return records
 
 
@@ -155,6 +171,8 @@ def main():
     ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16")
     ap.add_argument("--tile-order", choices=("default", "row_major", "grouped"), default="default",
                     help="tile index -> tile grid position for every plan (default: the library's choice per schedule)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time a HIP-graph replay of the launches instead of eager launches (no host launch floor)")
     ap.add_argument("--ascending", action="store_true",
                     help="Algorithm 1's order of a workgroup's Stream-K pieces instead of the k-aligned default")
     ap.add_argument("--fixup", choices=("flags", "atomic"), default="flags",
@@ -168,7 +186,7 @@ def main():
         shapes += [(M, N, K) for M in (16, 32, 64, 128) for N, K in ((8192, 8192), (4096, 4096), (16384, 4096))]
     tile = tuple(int(v) for v in args.tile.split(",")) if args.tile else None
     run(shapes, args.out, dtype_code=1 if args.dtype == "bf16" else 0, fixup=1 if args.fixup == "atomic" else 0, tile=tile, dp_first=args.dp_first, ascending=args.ascending,
-        tile_order={"default": None, "row_major": 0, "grouped": 1}[args.tile_order])
+        tile_order={"default": None, "row_major": 0, "grouped": 1}[args.tile_order], graph=args.graph)
     return 0
 
 
