@@ -108,10 +108,19 @@ def main():
         plans[p] = plan
     info = sk.sk_plan_info(plans[0])
 
+    bound = {}
+
     def launch(p, plan_set=None):
-        a, b, d = sets[launches[0] % len(sets)]
+        ps = plan_set or plans
+        i = launches[0] % len(sets)
         launches[0] += 1
-        sk.sk_gemm(a.data_ptr(), b.data_ptr(), d.data_ptr(), (plan_set or plans)[p], stream)
+        call = bound.get((id(ps), p, i))
+        if call is None:                       # arguments marshalled once per (plan, operand set)
+            a, b, d = sets[i]
+            call = bound[(id(ps), p, i)] = sk.sk_gemm_bind(a.data_ptr(), b.data_ptr(), d.data_ptr(), ps[p], stream)
+        status = call()
+        if status != sk.SK_OK:
+            raise sk.StreamKError(status, "sk_gemm")
 
     def time_policy(p, warm, timed, plan_set=None):
         """ms per launch: `timed` launches back to back between one pair of events, as the timed

@@ -204,6 +204,14 @@ def sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream=0):
     _check(_lib.sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream), "sk_gemm")
 
 
+def sk_gemm_bind(A_ptr, B_ptr, D_ptr, plan, stream=0):
+    """The same call with its arguments marshalled once: returns a function of no arguments that
+    enqueues the launch and returns the status code.  For loops that launch one problem many times
+    (the per-call conversion of five integers costs about as much as the launch itself)."""
+    import functools
+    return functools.partial(_lib.sk_gemm, _vp(A_ptr), _vp(B_ptr), _vp(D_ptr), _vp(plan), _vp(stream))
+
+
 def sk_gemm_status(A_ptr, B_ptr, D_ptr, plan, stream=0):
     """As sk_gemm but returns the status code instead of raising."""
     return _lib.sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream)
