@@ -955,11 +955,14 @@ template <class C, bool ATOMIC = false> KernelEntry* make_entry(int variant = 0)
 // alternative wave layouts / ring depths of the same shape, selectable with the environment
 // variable SK_KERNEL_VARIANT for tuning runs.  ATOMIC selects the atomic-add fix-up (sk_fixup).
 template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int* n) {
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 2, 32, 4>, ATOMIC>();
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>, ATOMIC>();
+    // The 128- and 64-row tiles run 8 waves (2 x 4), two per SIMD, like the large ones: with one wave
+    // per SIMD (2 x 2) nothing overlaps a wave's waits (128 x 128 x 64: +8 - 12 % on 512 x 8192 x 8192
+    // and 4096^3; 64 x 128 x 64: +4 % on the HBM-bound M = 64 shape, +12 - 20 % on small problems).
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 4, 32, 4>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 4, 32, 3>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>, ATOMIC>();
-    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 4, 32, 4>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>, ATOMIC>();
     if constexpr (!ATOMIC) {  // (the atomic fix-up exists for the layouts above only)
@@ -967,6 +970,8 @@ template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2>>(1);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 2, 2>>(2);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
+        t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>(1);
     }
 }
 

@@ -89,19 +89,19 @@ void expand_wg(const sk_plan_header& h, int x, std::vector<sk_segment>* out, sk_
 // plus 12 large skinny ones on MI355X (fit_tile_model.py; the fit optimises the dispatcher's pick,
 // not the predicted times, so the constants need not be physical).
 struct TileCost { int bm, bn; double tflops; };
-const TileCost tile_costs[] = {{256, 256, 990.}, {256, 128, 860.}, {128, 128, 719.}, {64, 128, 563.}, {32, 128, 434.}, {16, 128, 40.}};
+const TileCost tile_costs[] = {{256, 256, 976.}, {256, 128, 928.}, {128, 128, 848.}, {64, 128, 671.}, {32, 128, 464.}, {16, 128, 78.}};
 constexpr int MODEL_BK = 64, MODEL_GRID = 256;
 double model_iter_us(const TileCost& c, int bk) {          // one k-iteration of every workgroup of a full grid
     return 2.0 * c.bm * c.bn * bk * MODEL_GRID / (c.tflops * 1e12) * 1e6;
 }
-double model_tile_us(const TileCost& c) { return 1.40 + c.bm * c.bn * 2 / 61.8e3; }
+double model_tile_us(const TileCost& c) { return 0.63 + c.bm * c.bn * 2 / 54.8e3; }
 // exchange of partial tiles when about `split` workgroups share a tile: the partials an owner (or a
 // group leader) fetches one after the other - all of them up to 16 workgroups per tile, beyond that
 // the two-level reduction with groups of 8 where the kernel has one (two_level)
 double model_exchange_us(const TileCost& c, double split, bool two_level) {
     const bool tree = two_level && split >= 16;
     const double serial = tree ? 8 + split / 8 : split;
-    return 6.26 * (tree ? 2 : 1) + serial * c.bm * c.bn * 4 / 27.3e3;
+    return 2.64 * (tree ? 2 : 1) + serial * c.bm * c.bn * 4 / 59.9e3;
 }
 
 }  // namespace
