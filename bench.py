@@ -19,7 +19,7 @@ import numpy as np
 
 # HBM bytes per launch of each policy on the default workload (k-aligned segment order), from rocprofv3
 # FETCH_SIZE / WRITE_SIZE scaled by a plain-copy calibration (profiles/streamk_gemm_kernel_cfg2_bf16_3840x4224x4096.txt)
-MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.3e6 + 32.8e6, ("cfg2", "SK1_DP"): 406.6e6 + 64.1e6}
+MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.3e6 + 32.8e6, ("cfg2", "SK1_DP"): 404.6e6 + 64.0e6}
 MEASURED_TRAFFIC_BYTES.update({("cfg2", p): 452.1e6 + 64.1e6 for p in ("SK2_DP", "SK3_DP", "SK4_DP", "SK5_DP", "ALL_SK")})
 PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "e4m3": 5033.2}    # dense MFMA peak of MI355X
 
