@@ -270,6 +270,16 @@ int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* 
  * would read partial tiles too early.) */
 int sk_plan_check(const sk_plan_t* plan, void* stream);
 
+/* The kernel that sk_gemm would launch for this plan right now (host only, no GPU
+ * call): workgroup size in threads, dynamic LDS bytes per workgroup, and the
+ * variant number of the tile's kernel.  Variant 0 is the library's choice for a
+ * tile; the environment variable SK_KERNEL_VARIANT, read at every launch, asks
+ * for another wave layout of the same tile where one is compiled in (tuning
+ * runs; tiles without that variant keep variant 0).  Any out pointer may be
+ * NULL.  Errors: INVALID_ARG (NULL plan), UNSUPPORTED (no kernel for the plan's
+ * tile, input type and fix-up mode). */
+int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int32_t* lds_bytes, int32_t* variant);
+
 void sk_plan_destroy(sk_plan_t* plan);
 
 /* The tile shape the library picks for (M, N, K, in_dtype) when sk_config leaves

@@ -34,7 +34,7 @@ SK_STREAMK_FIRST, SK_DATA_PARALLEL_FIRST = 0, 1
 SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
-           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check",
+           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check", "sk_plan_kernel_info",
            "sk_plan_destroy", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
@@ -89,6 +89,7 @@ _lib.sk_plan_set_segment_order.argtypes = [_vp, _int]
 _lib.sk_plan_estimate_us.argtypes = [_vp, ctypes.POINTER(ctypes.c_double)]
 _lib.sk_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sk_plan_check.argtypes = [_vp, _vp]
+_lib.sk_plan_kernel_info.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int32)] * 3
 _lib.sk_plan_destroy.argtypes = [_vp]
 _lib.sk_plan_destroy.restype = None
 _lib.sk_default_tile.argtypes = [_i64, _i64, _i64, _int, ctypes.POINTER(ctypes.c_int32)]
@@ -219,6 +220,14 @@ def sk_gemm_status(A_ptr, B_ptr, D_ptr, plan, stream=0):
 
 def sk_plan_check(plan, stream=0):
     return _lib.sk_plan_check(plan, stream)
+
+
+def sk_plan_kernel_info(plan):
+    """{"threads", "lds_bytes", "variant"} of the kernel a launch of this plan would use now."""
+    v = (ctypes.c_int32 * 3)()
+    p = [ctypes.cast(ctypes.byref(v, 4 * i), ctypes.POINTER(ctypes.c_int32)) for i in range(3)]
+    _check(_lib.sk_plan_kernel_info(plan, *p), "sk_plan_kernel_info")
+    return {"threads": v[0], "lds_bytes": v[1], "variant": v[2]}
 
 
 def sk_plan_destroy(plan):

@@ -93,6 +93,18 @@ extern "C" int sk_plan_check(const sk_plan_t* plan, void* stream) {
     return SK_OK;
 }
 
+extern "C" int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int32_t* lds_bytes, int32_t* variant) {
+    if (!plan) return SK_ERR_INVALID_ARG;
+    const sk_plan_header& h = plan->h;
+    const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
+    const KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS);
+    if (!e) return SK_ERR_UNSUPPORTED;
+    if (threads) *threads = e->threads;
+    if (lds_bytes) *lds_bytes = e->lds_bytes;
+    if (variant) *variant = e->variant;
+    return SK_OK;
+}
+
 extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream) {
     if (!A || !B || !D || !plan) return SK_ERR_INVALID_ARG;
     const sk_plan_header& h = plan->h;

@@ -75,6 +75,29 @@ def test_integer_inputs_bit_exact_every_tile_and_policy(blk, dtype):
         _run_and_compare(A, B, dtype, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True)
 
 
+# wave layouts that are compiled in beside the default one of their tile (4 waves as 2 x 2; for the
+# 256 x 256 tile also 8 waves with two-stage rings), chosen with the environment variable SK_KERNEL_VARIANT
+VARIANT_TILES = [(1, (256, 128, 64)), (1, (256, 256, 64)), (1, (128, 128, 64)), (1, (64, 128, 64)), (2, (256, 256, 64))]
+
+
+@pytest.mark.parametrize("variant,blk", VARIANT_TILES)
+def test_alternative_wave_layouts_integer_exact(variant, blk, monkeypatch):
+    monkeypatch.setenv("SK_KERNEL_VARIANT", str(variant))      # read by the library at every launch
+    r = Runner(512, 512, 512, sk.SK_POLICY_DP, blk, 24, inputs.BF16, sk.SK_F32)
+    info = sk.sk_plan_kernel_info(r.plan)
+    r.close()
+    assert info["variant"] == variant and info["threads"] == (256 if variant == 1 else 512)
+    M, N, K = 2 * blk[0] + 40, 3 * blk[1] + 72, 5 * blk[2] + 24
+    A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 24)
+    ref = G.gemm_fp64(A, B, G.BF16)
+    for policy in range(8):
+        _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True)
+    A, B = inputs.uniform_pair(M, N, K, inputs.F16, 25)        # 16-bit epilogue, aligned and unaligned rows
+    _run_and_compare(A, B, inputs.F16, sk.SK_POLICY_ALL_SK, blk, grid=24)
+    A, B = inputs.uniform_pair(M + 3, N + 5, K + 1, inputs.BF16, 26)
+    _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_SK1_DP, blk, grid=24)
+
+
 @pytest.mark.parametrize("shape", [(77, 101, 203), (1, 64, 16), (5, 7, 3), (130, 129, 1), (300, 8, 2049), (16, 264, 520)])
 def test_ragged_and_unaligned_shapes(shape):
     M, N, K = shape
