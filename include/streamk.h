@@ -288,7 +288,8 @@ int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_
 
 /* The dispatcher's cost model applied to this plan: a rough time estimate in
  * microseconds (whole-tile waves, the evenly split Stream-K iterations, the
- * exchange of partial tiles), from constants fitted on MI355X.  Meant for ranking
+ * exchange of partial tiles: the chain of fetches of one owner plus the traffic
+ * of all contributors together), from constants fitted on MI355X.  Meant for ranking
  * the policies of one problem when no tuning record knows it (the selector's
  * fall-back when the Bloom filters of Sec. 4.2 return no candidate), not for
  * predicting times.  microseconds: host double.

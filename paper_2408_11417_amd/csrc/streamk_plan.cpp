@@ -123,6 +123,15 @@ extern "C" int sk_plan_estimate_us(const sk_plan_t* plan, double* microseconds) 
             double split = (double)h.iters_per_tile / h.iters_per_wg;     // workgroups per tile beyond the owner, about
             if (split < 1) split = 1;
             t += model_exchange_us(*c, split, !(c->bm == 256 && c->bn == 256));  // the 256 x 256 tile reduces in one level
+            // every workgroup that holds a contributor piece parks one fp32 tile and somebody fetches it, all at
+            // about the same time: that traffic shares the memory system (fitted: 6 TB/s for write plus read;
+            // with 256 x 256 tiles and a full grid it is 128 MB, the largest term of a short problem)
+            int64_t contributors = 0;
+            for (int64_t x = 0; x < h.grid; x++) {
+                const int64_t b = std::min<int64_t>(x * h.iters_per_wg, h.sk_iters), e = std::min<int64_t>((x + 1) * h.iters_per_wg, h.sk_iters);
+                if (e > b && (plan->k_aligned ? e : b) % h.iters_per_tile != 0) contributors++;
+            }
+            t += (double)contributors * c->bm * c->bn * 8 / 6.0e6;
         }
     }
     *microseconds = t;

@@ -284,6 +284,8 @@ def main():
     ap.add_argument("--tile-sweeps", nargs="*", default=[],
                     help="sweep files made with --tile, one per tile shape: evaluate tile-shape filters instead of policy filters")
     ap.add_argument("--split", type=int, default=400)
+    ap.add_argument("--held-sweeps", nargs="*", default=[],
+                    help="other sweep files: build from the first --split sizes of --sweep, hold out every size of these")
     ap.add_argument("--out", default="")
     args = ap.parse_args()
     if args.tile_sweeps:
@@ -300,6 +302,14 @@ def main():
             open(args.out, "w").write(text)
         return 0
     records = json.load(open(args.sweep))["records"]
+    if args.held_sweeps:
+        seen = {(r["M"], r["N"], r["K"]) for r in records[:args.split]}
+        records = records[:args.split]
+        for f in args.held_sweeps:
+            for r in json.load(open(f))["records"]:
+                if (r["M"], r["N"], r["K"]) not in seen:
+                    seen.add((r["M"], r["N"], r["K"]))
+                    records.append(r)
     report = {"statistics": sweep_statistics(records), "evaluations": []}
     for mode in ("exact", "shape"):
         for tol in (0.0, 0.05, 0.2):
