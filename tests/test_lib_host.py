@@ -290,6 +290,12 @@ def test_plan_estimate_properties():
     dp = est(4096 + 256, 4096, 4096, sk.SK_POLICY_DP, (256, 256, 64))   # 17 x 16 = 272 tiles
     sk2 = est(4096 + 256, 4096, 4096, sk.SK_POLICY_SK2_DP, (256, 256, 64))
     assert dp > 1.9 * one and one < sk2 < 1.3 * one
+    # 210 tiles of 256 x 256 over a short K: splitting saves a sixth of the iterations, but 250 workgroups
+    # then park and fetch a 256 KB partial tile each - measured 99 us against 64 us data-parallel
+    assert est(2560, 5280, 2160, sk.SK_POLICY_DP, blk) < est(2560, 5280, 2160, sk.SK_POLICY_ALL_SK, blk)
+    # ... while small tiles over a long K gain from the split (48 tiles of 32 x 128: 7.4 us against 9.0 us is
+    # a tie for the model, 128 iterations per tile are not)
+    assert est(512, 272, 8192, sk.SK_POLICY_ALL_SK, (32, 128, 64)) < est(512, 272, 8192, sk.SK_POLICY_DP, (32, 128, 64))
     # longer K costs more, bigger tiles cost more per tile
     assert est(4096, 4096, 8192, 0, blk) > one and est(4096, 4096, 4096, 0, (128, 128, 64)) > 0
     p = sk.sk_plan(4096, 4096, 4096, 0, (256, 256, 128), 256, sk.SK_FP8_E4M3, sk.SK_BF16)
