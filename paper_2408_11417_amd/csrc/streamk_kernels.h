@@ -720,14 +720,29 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
             } else {
                 blk = acc[mi][ni];
                 const float* src = part0 + ((mi * C::NI + ni) * C::ACC) * C::THREADS;
-                for (int c = 0; c < n_contrib; c++) {
+                // this block's share of GB contributors per round trip (GB * ACC registers of loads in
+                // flight), added in the same fixed order as one by one
+                constexpr int GB = 32 / C::ACC;
+                int c = 0;
+                for (; c + GB <= n_contrib; c += GB, src += GB * part_stride) {
+                    float v[GB][C::ACC];
+#pragma unroll
+                    for (int j = 0; j < GB; j++)
+#pragma unroll
+                        for (int r = 0; r < C::ACC; r++)
+                            v[j][r] = __hip_atomic_load(src + j * part_stride + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int j = 0; j < GB; j++)
+#pragma unroll
+                        for (int r = 0; r < C::ACC; r++) blk[r] += v[j][r];
+                }
+                for (; c < n_contrib; c++, src += part_stride) {
                     float v[C::ACC];
 #pragma unroll
                     for (int r = 0; r < C::ACC; r++)
                         v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                     for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
-                    src += part_stride;
                 }
             }
             store_block<C, OUT, EDGE, TR>(g, row0 + mi * C::MF, col0 + ni * C::MF, blk);
