@@ -319,7 +319,10 @@ def test_paper_suite_shapes_fp16_sampled_rows(shape):
 
 @pytest.mark.parametrize("blk,shape", [((32, 128, 64), (64, 208, 7872)), ((16, 128, 64), (48, 256, 6208)),
                                        ((64, 128, 64), (128, 128, 16448)), ((128, 128, 64), (128, 256, 8256)),
-                                       ((32, 128, 64), (32, 1024, 4160)), (None, (112, 128, 3552))])
+                                       ((32, 128, 64), (32, 1024, 4160)), (None, (112, 128, 3552)),
+                                       # 128 accumulators per lane: reduced block by block, two contributors per
+                                       # round trip; 32 - 33 contributors per tile, then 67 (an odd one left over)
+                                       ((256, 256, 64), (300, 512, 4160)), ((256, 256, 64), (256, 256, 4352))])
 def test_tiles_shared_by_many_workgroups(blk, shape):
     # few tiles, long K: 16 ... 120 contributors per tile, reduced in two levels (groups of 8 behind a leader)
     M, N, K = shape
