@@ -591,11 +591,48 @@ __device__ __forceinline__ void wait_flags(const GemmArgs& g, int first, int cou
     }
 }
 
+// blk += this block's share of the parked partial tiles src, src + stride, ... (`count` of them), in
+// that order, GB contributors per round trip (GB * ACC registers of loads in flight).
+template <class C, int GB>
+__device__ __forceinline__ void add_block_partials(typename Mfma<C::DT, C::MF>::Acc& blk, const float* src, int count, ptrdiff_t stride) {
+    int c = 0;
+    for (; c + GB <= count; c += GB, src += GB * stride) {
+        float v[GB][C::ACC];
+#pragma unroll
+        for (int j = 0; j < GB; j++)
+#pragma unroll
+            for (int r = 0; r < C::ACC; r++)
+                v[j][r] = __hip_atomic_load(src + j * stride + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < GB; j++)
+#pragma unroll
+            for (int r = 0; r < C::ACC; r++) blk[r] += v[j][r];
+    }
+    for (; c < count; c++, src += stride) {
+        float v[C::ACC];
+#pragma unroll
+        for (int r = 0; r < C::ACC; r++)
+            v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
+    }
+}
+
 // sum += the parked partial tiles src, src + stride, ... (`count` of them, this lane's share), in
-// that order.  For tiles with at most 64 accumulators per lane: a contributor's whole share is
+// that order.  Tiles with at most 64 accumulators per lane: a contributor's whole share is
 // fetched at once and G contributors per round trip (about 64 registers of loads in flight).
+// Bigger tiles: block by block, the shares of two contributors per round trip.
 template <class C>
 __device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&sum)[C::MI][C::NI], const float* src, int count, ptrdiff_t stride) {
+    if constexpr (C::ACC_REGS > 64) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ni++) {
+                add_block_partials<C, 32 / C::ACC>(sum[mi][ni], src + ((mi * C::NI + ni) * C::ACC) * C::THREADS, count, stride);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    } else {
     constexpr int G = 64 / C::ACC_REGS < 8 ? 64 / C::ACC_REGS : 8;
     auto add_group = [&](const float* p, auto cnt) {
         constexpr int CNT = decltype(cnt)::value;
@@ -617,6 +654,7 @@ __device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&
     int c = 0;
     for (; c + G <= count; c += G, src += G * stride) add_group(src, std::integral_constant<int, G>());
     for (; c < count; c++, src += stride) add_group(src, std::integral_constant<int, 1>());
+    }
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return (uint32_t)to_bf16_bits(lo) | ((uint32_t)to_bf16_bits(hi) << 16); }
@@ -720,30 +758,9 @@ __device__ __forceinline__ void reduce_and_store(const GemmArgs& g, int row0, in
             } else {
                 blk = acc[mi][ni];
                 const float* src = part0 + ((mi * C::NI + ni) * C::ACC) * C::THREADS;
-                // this block's share of GB contributors per round trip (GB * ACC registers of loads in
-                // flight), added in the same fixed order as one by one
-                constexpr int GB = 32 / C::ACC;
-                int c = 0;
-                for (; c + GB <= n_contrib; c += GB, src += GB * part_stride) {
-                    float v[GB][C::ACC];
-#pragma unroll
-                    for (int j = 0; j < GB; j++)
-#pragma unroll
-                        for (int r = 0; r < C::ACC; r++)
-                            v[j][r] = __hip_atomic_load(src + j * part_stride + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                    for (int j = 0; j < GB; j++)
-#pragma unroll
-                        for (int r = 0; r < C::ACC; r++) blk[r] += v[j][r];
-                }
-                for (; c < n_contrib; c++, src += part_stride) {
-                    float v[C::ACC];
-#pragma unroll
-                    for (int r = 0; r < C::ACC; r++)
-                        v[r] = __hip_atomic_load(src + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                    for (int r = 0; r < C::ACC; r++) blk[r] += v[r];
-                }
+                // two contributors' shares of this block per round trip (all the registers allow), added in
+                // the same fixed order as one by one
+                add_block_partials<C, 32 / C::ACC>(blk, src, n_contrib, part_stride);
             }
             store_block<C, OUT, EDGE, TR>(g, row0 + mi * C::MF, col0 + ni * C::MF, blk);
             __builtin_amdgcn_sched_barrier(0);
@@ -860,14 +877,13 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         }
 
         // ---- fix-up
-        // Tiles shared by many workgroups are reduced in two levels (TREE; small tiles only, the
-        // big ones never have that many contributors): every SK_TREE_GROUP-th contributor first
+        // Tiles shared by many workgroups are reduced in two levels: every SK_TREE_GROUP-th contributor first
         // adds the partials of the contributors behind it to its own accumulators, so the owner
         // collects one partial per group.  The order of the additions stays fixed.
         // The owner of a split tile is the workgroup holding its first iteration, the contributors
         // are the workgroups after it (dir = +1); in the k-aligned order the one holding its last
         // iteration, which finishes last, and the contributors are the workgroups before it (dir = -1).
-        constexpr bool TREE = C::ACC_REGS <= 64;
+        constexpr bool TREE = true;
         const bool split = k_begin > 0 || k_end < g.ipt;
         const bool contributor = g.k_aligned ? k_end < g.ipt : k_begin > 0;
         const int dir = g.k_aligned ? -1 : 1;

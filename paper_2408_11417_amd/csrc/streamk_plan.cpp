@@ -97,9 +97,9 @@ double model_iter_us(const TileCost& c, int bk) {          // one k-iteration of
 double model_tile_us(const TileCost& c) { return 0.63 + c.bm * c.bn * 2 / 54.8e3; }
 // exchange of partial tiles when about `split` workgroups share a tile: the partials an owner (or a
 // group leader) fetches one after the other - all of them up to 16 workgroups per tile, beyond that
-// the two-level reduction with groups of 8 where the kernel has one (two_level)
-double model_exchange_us(const TileCost& c, double split, bool two_level) {
-    const bool tree = two_level && split >= 16;
+// the two-level reduction with groups of 8
+double model_exchange_us(const TileCost& c, double split) {
+    const bool tree = split >= 16;
     const double serial = tree ? 8 + split / 8 : split;
     return 2.64 * (tree ? 2 : 1) + serial * c.bm * c.bn * 4 / 59.9e3;
 }
@@ -122,7 +122,7 @@ extern "C" int sk_plan_estimate_us(const sk_plan_t* plan, double* microseconds) 
         if (plan->needs_fixup) {
             double split = (double)h.iters_per_tile / h.iters_per_wg;     // workgroups per tile beyond the owner, about
             if (split < 1) split = 1;
-            t += model_exchange_us(*c, split, !(c->bm == 256 && c->bn == 256));  // the 256 x 256 tile reduces in one level
+            t += model_exchange_us(*c, split);
             // every workgroup that holds a contributor piece parks one fp32 tile and somebody fetches it, all at
             // about the same time: that traffic shares the memory system (fitted: 6 TB/s for write plus read;
             // with 256 x 256 tiles and a full grid it is 128 MB, the largest term of a short problem)
@@ -166,7 +166,7 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
         if (split > ipt) split = ipt;
         if (split < 1) split = 1;
         double t_sk = ipw * t_iter + c_tile * (tiles > grid ? tiles / grid : 1.0);
-        if (((int64_t)tiles % grid) != 0) t_sk += model_exchange_us(c, split, true);
+        if (((int64_t)tiles % grid) != 0) t_sk += model_exchange_us(c, split);
         const double t = t_dp < t_sk ? t_dp : t_sk;
         if (best < 0 || t < best_t) { best = i; best_t = t; }
     }
