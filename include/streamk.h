@@ -71,7 +71,9 @@ typedef enum {
 /* How the partial results of a split tile are combined.
  * FLAGS (default): the workspace-and-flags exchange described at sk_role, the
  * alternative Sec. 5.3 names; the owner adds the partials in a fixed order
- * (see sk_segment_order), so D is bit-identical from run to run.
+ * (see sk_segment_order; when 16 or more workgroups share a tile, in two
+ * levels: every 8th contributor first adds the partials of the 7 behind it to
+ * its own and parks the sum), so D is bit-identical from run to run.
  * ATOMIC: the accumulation step of Algorithm 1, as printed: every workgroup that holds only
  * part of a tile's K-iterations adds its accumulators into a zero-initialised
  * fp32 image of D with atomic adds, nobody waits for anybody.  The order of the
