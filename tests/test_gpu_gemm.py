@@ -189,6 +189,18 @@ def test_fp8_integer_inputs_bit_exact(blk):
         _run_and_compare(A, B, inputs.E4M3, policy, blk, grid=16, out_dtype=sk.SK_F32, ref=ref, exact=True)
 
 
+@pytest.mark.parametrize("blk,shape", [((256, 256, 128), (256, 512, 8448)), ((128, 256, 128), (128, 256, 8704))])
+def test_fp8_tiles_shared_by_many_workgroups(blk, shape):
+    # 65 and 67 contributors per tile: two-level reduction, block by block for the 256 x 256 tile
+    M, N, K = shape
+    A, B = inputs.small_int_pair(M, N, K, inputs.E4M3, 34)
+    ref = G.gemm_fp64(A, B, G.E4M3)
+    for policy in (sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
+        _run_and_compare(A, B, inputs.E4M3, policy, blk, grid=256, out_dtype=sk.SK_F32, ref=ref, exact=True, launches=2)
+    _run_and_compare(A, B, inputs.E4M3, sk.SK_POLICY_ALL_SK, blk, grid=256, out_dtype=sk.SK_F32, ref=ref, exact=True, k_aligned=False)
+    _run_and_compare(A, B, inputs.E4M3, sk.SK_POLICY_ALL_SK, blk, grid=256, ref=ref)          # bf16 output
+
+
 def test_fp8_uniform_inputs_medium():
     A, B = inputs.uniform_pair(520, 776, 1040, inputs.E4M3, 33)
     ref = G.gemm_fp64(A, B, G.E4M3)
