@@ -883,7 +883,6 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         // The owner of a split tile is the workgroup holding its first iteration, the contributors
         // are the workgroups after it (dir = +1); in the k-aligned order the one holding its last
         // iteration, which finishes last, and the contributors are the workgroups before it (dir = -1).
-        constexpr bool TREE = true;
         const bool split = k_begin > 0 || k_end < g.ipt;
         const bool contributor = g.k_aligned ? k_end < g.ipt : k_begin > 0;
         const int dir = g.k_aligned ? -1 : 1;
@@ -894,18 +893,16 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             n_all = last_wg - first_wg;
             j = g.k_aligned ? last_wg - x : x - first_wg;
         }
-        const bool two_level = TREE && n_all >= 2 * SK_TREE_GROUP;
+        const bool two_level = n_all >= 2 * SK_TREE_GROUP;
         const ptrdiff_t slot_stride = (ptrdiff_t)dir * (C::BM * C::BN);
         if (contributor) {
-            if constexpr (TREE) {
-                if (two_level && (j - 1) % SK_TREE_GROUP == 0) {        // group leader: members j+1 .. j+GROUP-1
-                    const int members = (j + SK_TREE_GROUP - 1 <= n_all ? j + SK_TREE_GROUP - 1 : n_all) - j;
-                    if (wave == 0) wait_flags(g, x + dir, members, dir);
-                    __syncthreads();
-                    const float* mp = g.partials + (ptrdiff_t)(x + dir) * (C::BM * C::BN) + tid;
-                    asm volatile("" : "+v"(mp));
-                    add_partials<C>(acc, mp, members, slot_stride);
-                }
+            if (two_level && (j - 1) % SK_TREE_GROUP == 0) {            // group leader: members j+1 .. j+GROUP-1
+                const int members = (j + SK_TREE_GROUP - 1 <= n_all ? j + SK_TREE_GROUP - 1 : n_all) - j;
+                if (wave == 0) wait_flags(g, x + dir, members, dir);
+                __syncthreads();
+                const float* mp = g.partials + (ptrdiff_t)(x + dir) * (C::BM * C::BN) + tid;
+                asm volatile("" : "+v"(mp));
+                add_partials<C>(acc, mp, members, slot_stride);
             }
             // park the accumulators (register order, coalesced), then signal.
             // Partial tiles are stored and loaded with device-scope atomic accesses (one dword
