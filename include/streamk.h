@@ -71,7 +71,7 @@ typedef enum {
 /* How the partial results of a split tile are combined.
  * FLAGS (default): the workspace-and-flags exchange described at sk_role, the
  * alternative Sec. 5.3 names; the owner adds the partials in a fixed order
- * (see sk_segment_order; when 16 or more workgroups share a tile, in two
+ * (see sk_segment_order; when a tile has 16 or more contributors, in two
  * levels: every 8th contributor first adds the partials of the 7 behind it to
  * its own and parks the sum), so D is bit-identical from run to run.
  * ATOMIC: the accumulation step of Algorithm 1, as printed: every workgroup that holds only
@@ -272,14 +272,18 @@ int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* 
  * would read partial tiles too early.) */
 int sk_plan_check(const sk_plan_t* plan, void* stream);
 
+/* Ask for another compiled wave layout of the plan's tile (a tuning knob of the dispatcher,
+ * Sec. 4.1: one kernel instance per tile configuration).  Variant 0 is the library's choice for
+ * every tile; where a tile has further layouts compiled in (e.g. four waves instead of eight per
+ * workgroup) they are numbered from 1; a tile without the requested variant keeps variant 0.
+ * The results are the same under every variant.  Errors: INVALID_ARG (NULL plan, negative number). */
+int sk_plan_set_kernel_variant(sk_plan_t* plan, int variant);
+
 /* The kernel that sk_gemm would launch for this plan right now (host only, no GPU
  * call): workgroup size in threads, dynamic LDS bytes per workgroup, and the
- * variant number of the tile's kernel.  Variant 0 is the library's choice for a
- * tile; the environment variable SK_KERNEL_VARIANT, read at every launch, asks
- * for another wave layout of the same tile where one is compiled in (tuning
- * runs; tiles without that variant keep variant 0).  Any out pointer may be
- * NULL.  Errors: INVALID_ARG (NULL plan), UNSUPPORTED (no kernel for the plan's
- * tile, input type and fix-up mode). */
+ * variant number of the tile's kernel (see sk_plan_set_kernel_variant).  Any out
+ * pointer may be NULL.  Errors: INVALID_ARG (NULL plan), UNSUPPORTED (no kernel for
+ * the plan's tile, input type and fix-up mode). */
 int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int32_t* lds_bytes, int32_t* variant);
 
 void sk_plan_destroy(sk_plan_t* plan);

@@ -15,7 +15,7 @@ except ImportError:
     pass
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("STREAMK_LIB") or os.path.join(_HERE, "libstreamk.so")   # override: tuning builds
+LIB_PATH = os.path.join(_HERE, "libstreamk.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError("libstreamk.so is not built: run `python -m paper_2408_11417_amd.build`")
 _lib = ctypes.CDLL(LIB_PATH)
@@ -34,7 +34,7 @@ SK_STREAMK_FIRST, SK_DATA_PARALLEL_FIRST = 0, 1
 SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
-           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_gemm", "sk_plan_check", "sk_plan_kernel_info",
+           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_plan_set_kernel_variant", "sk_gemm", "sk_plan_check", "sk_plan_kernel_info",
            "sk_plan_destroy", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
@@ -83,6 +83,7 @@ _lib.sk_workspace_bytes.argtypes = [_vp]
 _lib.sk_workspace_bytes.restype = ctypes.c_size_t
 _lib.sk_plan_set_workspace.argtypes = [_vp, _vp, ctypes.c_size_t]
 _lib.sk_plan_set_spin_limit.argtypes = [_vp, ctypes.c_uint32]
+_lib.sk_plan_set_kernel_variant.argtypes = [_vp, _int]
 _lib.sk_plan_set_fixup.argtypes = [_vp, _int]
 _lib.sk_plan_set_batch_order.argtypes = [_vp, _int]
 _lib.sk_plan_set_segment_order.argtypes = [_vp, _int]
@@ -198,6 +199,10 @@ def sk_plan_set_segment_order(plan, segment_order):
 
 def sk_plan_set_spin_limit(plan, polls):
     _check(_lib.sk_plan_set_spin_limit(plan, polls), "sk_plan_set_spin_limit")
+
+
+def sk_plan_set_kernel_variant(plan, variant):
+    _check(_lib.sk_plan_set_kernel_variant(plan, variant), "sk_plan_set_kernel_variant")
 
 
 def sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream=0):

@@ -1,5 +1,4 @@
 // Host side of the Stream-K GEMM: kernel table, workspace handling and the sk_gemm launcher.
-#include <cstdlib>
 #include <mutex>
 #include "streamk_kernels.h"
 
@@ -13,23 +12,21 @@ KernelEntry** kernel_table(int* count) {
     static std::once_flag once;
     std::call_once(once, [] {
         register_bf16(table, &n);
-#ifndef SK_ONLY_BF16   // (tuning builds that compile one input type only)
         register_f16(table, &n);
         register_fp8(table, &n);
         register_bf16_atomic(table, &n);
         register_f16_atomic(table, &n);
         register_fp8_atomic(table, &n);
-#endif
     });
     *count = n;
     return table;
 }
 
-KernelEntry* find_kernel(int dtype, int bm, int bn, int bk, int fixup = SK_FIXUP_FLAGS) {
+// The kernel for a tile shape, input type and fix-up mode: the wanted variant if the shape has it,
+// else the shape's variant 0.
+KernelEntry* find_kernel(int dtype, int bm, int bn, int bk, int fixup = SK_FIXUP_FLAGS, int want = 0) {
     int n;
     KernelEntry** t = kernel_table(&n);
-    const char* env = getenv("SK_KERNEL_VARIANT");
-    const int want = env ? atoi(env) : 0;
     KernelEntry* fallback = nullptr;
     for (int i = 0; i < n; i++)
         if (t[i]->dtype == dtype && t[i]->bm == bm && t[i]->bn == bn && t[i]->bk == bk && t[i]->fixup == fixup) {
@@ -97,7 +94,7 @@ extern "C" int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int3
     if (!plan) return SK_ERR_INVALID_ARG;
     const sk_plan_header& h = plan->h;
     const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
-    const KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS);
+    const KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant);
     if (!e) return SK_ERR_UNSUPPORTED;
     if (threads) *threads = e->threads;
     if (lds_bytes) *lds_bytes = e->lds_bytes;
@@ -115,7 +112,7 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
         return SK_ERR_UNSUPPORTED;
     // plans without split tiles run the plain kernel under either fix-up mode
     const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
-    KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS);
+    KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant);
     if (!e) return SK_ERR_UNSUPPORTED;
     if (plan->needs_fixup && !plan->workspace && !(atomic && h.out_dtype == SK_F32)) return SK_ERR_WORKSPACE;
     const bool aligned = (h.K % e->piece_elems == 0) && (h.N % e->piece_elems == 0);   // whole 16-byte pieces per row

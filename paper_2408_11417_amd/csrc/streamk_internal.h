@@ -13,6 +13,7 @@ struct sk_plan_t {
     int fixup = SK_FIXUP_FLAGS;     // how split tiles are combined
     int dp_first = 0;               // 1: data-parallel tiles before the Stream-K iterations
     int k_aligned = 1;              // 1: head piece of a Stream-K range first, last workgroup of a tile owns it
+    int kernel_variant = 0;         // which compiled wave layout of the tile's kernel to launch (0 = the library's choice)
 };
 
 // Workspace layout: [grid flag lines of SK_FLAG_STRIDE bytes][status line][partials]

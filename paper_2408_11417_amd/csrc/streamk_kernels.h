@@ -26,6 +26,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -103,7 +106,7 @@ template <> struct Mfma<SK_FP8_E4M3, 16> {
     }
 };
 
-template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MF_, int NSA_, int NSB_ = NSA_>
+template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int MF_, int NSA_, int NSB_ = NSA_, int FINE_ = 0>
 struct Cfg {
     static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MF = MF_;
     static constexpr int NSA = NSA_, NSB = NSB_;        // LDS ring depth of the A and of the B tiles
@@ -139,6 +142,12 @@ struct Cfg {
     // k-step's operands, then multiply the current ones".
     static constexpr int FRAG_REGS = (MI + NI) * (FP8 ? 8 : 4), ACC_REGS = MI * NI * ACC;
     static constexpr bool PIN_ORDER = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 64 <= 256 : 2 * FRAG_REGS + 64 <= 160;
+    // FINE: the MAC loop is written out instruction by instruction - one matrix-core instruction, then
+    // at most a few LDS reads of the next k-step's operands or one LDS-DMA request, and so on - so that
+    // a wave that has a SIMD to itself keeps the matrix-core pipe fed while its memory instructions
+    // queue up (needs the two operand sets of PIN_ORDER).
+    static constexpr bool FINE = FINE_ != 0;
+    static_assert(!FINE || PIN_ORDER, "the instruction-by-instruction order needs two operand sets");
     // register-staged path: room to hold the next stage's pieces (4 registers each) during the matrix-core work
     static constexpr bool STAGE_AHEAD = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 4 * (CA + CB) + 64 <= 256 : 2 * FRAG_REGS + 4 * (CA + CB) + 64 <= 224;
     static_assert(WTM % MF == 0 && WTN % MF == 0 && BK % KM == 0, "tile does not divide");
@@ -183,6 +192,9 @@ static __device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
 // 16 bytes global -> LDS without passing through registers.  The LDS destination of lane l is
 // lds_base + 16 * l; lds_base must be wave-uniform.  Completion is tracked by vmcnt only; the
 // compiler is not told that LDS is written: the caller orders the reads with s_waitcnt + barrier.
+// m0 is not named as clobbered: it is a reserved register for this compiler (it never holds a value of
+// the program across statements; the compiler writes it right before an instruction of its own that
+// reads it), and naming a reserved register in a clobber list is rejected as undefined behaviour.
 __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base));
 }
@@ -371,6 +383,19 @@ template <class C> struct FragMap {
 template <class C, bool FP8 = C::FP8> struct Frags;
 template <class C> struct Frags<C, false> {
     uint4 a[C::MI], b[C::NI];
+    // The LDS reads of one k-step one at a time, in the order in which the matrix-core work needs
+    // them (block row 0, all block columns, the other block rows): read number r of READS.
+    static constexpr int READS = C::MI + 2 * C::NI;
+    __device__ __forceinline__ void load_one(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk, int r) {
+        if (r == 0 || r > 2 * C::NI) {
+            const int mi = r == 0 ? 0 : r - 2 * C::NI;
+            a[mi] = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][0] + mi * C::MF * C::CPA * 16);
+        } else {
+            const int ni = (r - 1) / 2, h = (r - 1) % 2;
+            const uint2 v = read_b_tr16(b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16 + h * 4 * C::CPB * 16);
+            if (h == 0) { b[ni].x = v.x; b[ni].y = v.y; } else { b[ni].z = v.x; b[ni].w = v.y; }
+        }
+    }
     __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
 #pragma unroll
         for (int mi = 0; mi < C::MI; mi++)
@@ -385,6 +410,18 @@ template <class C> struct Frags<C, false> {
 };
 template <class C> struct Frags<C, true> {
     i32x8 a[C::MI], b[C::NI];
+    static constexpr int READS = 2 * C::MI + 4 * C::NI;
+    __device__ __forceinline__ void load_one(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk, int r) {
+        if (r < 2 || r >= 2 + 4 * C::NI) {
+            const int mi = r < 2 ? 0 : (r - 4 * C::NI) / 2, h = r % 2;
+            const uint4 v = *reinterpret_cast<const uint4*>(a_stage + fm.a_kk[kk][h] + mi * C::MF * C::CPA * 16);
+            a[mi][4 * h] = (int)v.x; a[mi][4 * h + 1] = (int)v.y; a[mi][4 * h + 2] = (int)v.z; a[mi][4 * h + 3] = (int)v.w;
+        } else {
+            const int ni = (r - 2) / 4, q = (r - 2) % 4;
+            const i32x2 v = read_b_tr8(b_stage + fm.b_ni[ni] + kk * C::KM * C::CPB * 16 + q * 8 * C::CPB * 16);
+            b[ni][2 * q] = v[0]; b[ni][2 * q + 1] = v[1];
+        }
+    }
     __device__ __forceinline__ void load(const unsigned char* a_stage, const unsigned char* b_stage, const FragMap<C>& fm, int kk) {
 #pragma unroll
         for (int mi = 0; mi < C::MI; mi++) {
@@ -403,9 +440,7 @@ template <class C> struct Frags<C, true> {
 };
 
 __device__ __forceinline__ u16 to_bf16_bits(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u16)((u >> 16) | 0x40);   // quiet NaN
-    return (u16)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);                   // round to nearest even
+    return __builtin_bit_cast(u16, (__bf16)f);     // round to nearest even (one hardware instruction on gfx950)
 }
 
 template <class C, int LATER> __device__ __forceinline__ void wait_stage(int later) {
@@ -493,6 +528,27 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         // bookkeeping merges conservatively at joins) - and scheduling barriers keep the reads of
         // k-step kk+1 ahead of the matrix-core work of k-step kk.  Otherwise the compiler is left
         // to order reads and matrix-core work so that one operand set suffices.
+        // FINE: one k-step written out slot by slot.  Slot s = [matrix-core instruction s of the k-step
+        // on operand set `cur`] [its share of the LDS reads that fill `nxt` with the operands of k-step
+        // kk_next of stage i+1: the reads go into the first three quarters of the slots, so that the
+        // last of them has long landed when the k-step ends] [its share of request batch i, spread
+        // evenly over all slots of the trip].  A scheduling barrier after every slot keeps that order.
+        auto fine_step = [&](int i, int step, auto mma, auto read, const Frags<C>& cur, Frags<C>& nxt,
+                             const unsigned char* a_next, const unsigned char* b_next, int kk_next, auto steady) {
+            constexpr int NM = C::MI * C::NI, R = Frags<C>::READS, NRS = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
+#pragma unroll
+            for (int s = 0; s < NM; s++) {
+                const int mi = s / C::NI, ni = s % C::NI;
+                if (decltype(mma)::value)
+                    acc[mi][ni] = TR ? Mfma<C::DT, C::MF>::run(cur.b[ni], cur.a[mi], acc[mi][ni]) : Mfma<C::DT, C::MF>::run(cur.a[mi], cur.b[ni], acc[mi][ni]);
+                if (decltype(read)::value && s < NRS) {
+#pragma unroll
+                    for (int r = s * R / NRS; r < (s + 1) * R / NRS; r++) nxt.load_one(a_next, b_next, fm, kk_next, r);
+                }
+                issue_batch(i, ca, cb, step * NM + s, C::KK * NM, steady);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
         auto trip = [&](int i, auto first, auto next, auto steady) {
             constexpr bool FIRST = decltype(first)::value;
             constexpr bool STEADY = decltype(steady)::value;     // batch i's stages exist and need no K-tail handling, and at least NSA - 1 stages follow stage i + 1
@@ -501,6 +557,25 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
             const int na = ca + 1 == C::NSA ? 0 : ca + 1, nb = cb + 1 == C::NSB ? 0 : cb + 1;   // slots of stage i+1
             const unsigned char* a_next = smem + na * C::A_BYTES;
             const unsigned char* b_next = smem + C::B_RING + nb * C::B_BYTES;
+            if constexpr (C::FINE) {
+                static_assert(!C::FINE || NEXT >= 0, "known at compile time under PIN_ORDER");
+                if (NEXT) {
+                    if (STEADY) wait_vmcnt<C::in_flight(C::NSA - 1)>();
+                    else wait_stage<C, C::NSA - 1>(nk - 2 - i);
+                    __syncthreads();
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // last k-step of stage i, with the reads of stage i+1's first k-step
+                fine_step(i, 0, std::integral_constant<bool, !FIRST>(), std::integral_constant<bool, NEXT == 1>(), f[1], f[0], a_next, b_next, 0, steady);
+                if (NEXT) {
+#pragma unroll
+                    for (int kk = 0; kk < C::KK - 1; kk++)
+                        fine_step(i, kk + 1, std::true_type(), std::true_type(), f[kk & 1], f[(kk + 1) & 1], a_next, b_next, kk + 1, steady);
+                }
+                ca = na;
+                cb = nb;
+                return;
+            }
             if (has_next) {
                 if (STEADY) wait_vmcnt<C::in_flight(C::NSA - 1)>();
                 else wait_stage<C, C::NSA - 1>(nk - 2 - i);   // stage i+1 has landed (this wave's share)
@@ -530,7 +605,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         // range checks nor the K-tail variant of the requests, and waits with a constant count.
         int n_steady = (full_k - k_begin < nk ? full_k - k_begin : nk) - C::NSA;
         if (n_steady < 0) n_steady = 0;
-        if (C::PIN_ORDER) {
+        if constexpr (C::PIN_ORDER) {
             trip(-1, std::true_type(), Yes(), std::false_type());
             int i = 0;
             for (; i < n_steady; i++) trip(i, std::false_type(), Yes(), std::true_type());
@@ -657,9 +732,13 @@ __device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&
     }
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return (uint32_t)to_bf16_bits(lo) | ((uint32_t)to_bf16_bits(hi) << 16); }
+// Two fp32 values -> one register of two 16-bit values, round to nearest even (gfx950 converts a
+// pair to bf16 with one instruction).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2{lo, hi}), bf16x2));
+}
 __device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
-    return (uint32_t)__builtin_bit_cast(u16, (_Float16)lo) | ((uint32_t)__builtin_bit_cast(u16, (_Float16)hi) << 16);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2{lo, hi}), f16x2));
 }
 
 // Convert and store one accumulator block.
@@ -979,24 +1058,26 @@ template <class C, bool ATOMIC = false> KernelEntry* make_entry(int variant = 0)
 }
 
 // Tile shapes with a kernel: <dtype, BM, BN, BK, waves along M, waves along N, matrix-core block,
-// A ring depth[, B ring depth]>.  Variant 0 of a shape is the one sk_gemm uses; other variants are
-// alternative wave layouts / ring depths of the same shape, selectable with the environment
-// variable SK_KERNEL_VARIANT for tuning runs.  ATOMIC selects the atomic-add fix-up (sk_fixup).
+// A ring depth[, B ring depth[, instruction-by-instruction MAC loop]]>.  Variant 0 of a shape is the
+// one sk_gemm uses; other variants are alternative wave layouts of the same shape, selectable with
+// sk_plan_set_kernel_variant for tuning runs.  ATOMIC selects the atomic-add fix-up (sk_fixup).
 template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int* n) {
     // The 128- and 64-row tiles run 8 waves (2 x 4), two per SIMD, like the large ones: with one wave
     // per SIMD (2 x 2) nothing overlaps a wave's waits (128 x 128 x 64: +8 - 12 % on 512 x 8192 x 8192
     // and 4096^3; 64 x 128 x 64: +4 % on the HBM-bound M = 64 shape, +12 - 20 % on small problems).
+    // The three compute-bound shapes run the instruction-by-instruction MAC loop (+5 % on 8192^3 with
+    // 256 x 256, +8 % on 4096^3 with 128 x 128, +2 - 3 % with 256 x 128; the 64-row tile loses 7 % with it).
     t[(*n)++] = make_entry<Cfg<DT, 128, 128, 32, 2, 4, 32, 4>, ATOMIC>();
-    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 4, 32, 3>, ATOMIC>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3>, ATOMIC>();
-    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 4, 32, 3, 3, 1>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3, 3, 1>, ATOMIC>();
+    t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2, 1>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 4, 32, 4>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>, ATOMIC>();
     if constexpr (!ATOMIC) {  // (the atomic fix-up exists for the layouts above only)
         t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>(1);
-        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2>>(1);
-        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 2, 2>>(2);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2, 1>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>(2);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
         t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>(1);
         t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>(1);

@@ -379,6 +379,12 @@ extern "C" int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls) {
     return SK_OK;
 }
 
+extern "C" int sk_plan_set_kernel_variant(sk_plan_t* plan, int variant) {
+    if (!plan || variant < 0) return SK_ERR_INVALID_ARG;
+    plan->kernel_variant = variant;
+    return SK_OK;
+}
+
 extern "C" void sk_plan_destroy(sk_plan_t* plan) { delete plan; }
 
 extern "C" const char* sk_status_str(int status) {

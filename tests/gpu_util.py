@@ -18,12 +18,13 @@ class Runner:
     """One plan with its workspace; run() launches sk_gemm on torch's current stream."""
 
     def __init__(self, M, N, K, policy, blk=None, grid=0, in_dtype=sk.SK_BF16, out_dtype=None, tile_order=None,
-                 fixup=sk.SK_FIXUP_FLAGS, dp_first=False, k_aligned=True):
+                 fixup=sk.SK_FIXUP_FLAGS, dp_first=False, k_aligned=True, variant=0):
         self.plan = sk.sk_plan(M, N, K, policy, blk, grid, in_dtype, out_dtype, tile_order)
         sk.sk_plan_set_fixup(self.plan, fixup)
         if dp_first:
             sk.sk_plan_set_batch_order(self.plan, sk.SK_DATA_PARALLEL_FIRST)
         sk.sk_plan_set_segment_order(self.plan, sk.SK_SEGMENTS_K_ALIGNED if k_aligned else sk.SK_SEGMENTS_ASCENDING)
+        sk.sk_plan_set_kernel_variant(self.plan, variant)
         self.info = sk.sk_plan_info(self.plan)
         nbytes = sk.sk_workspace_bytes(self.plan)
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")

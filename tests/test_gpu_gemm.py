@@ -20,12 +20,12 @@ ODT = {inputs.F16: G.F16, inputs.BF16: G.BF16, inputs.E4M3: G.E4M3}
 
 
 def _run_and_compare(A, B, dtype, policy, blk, grid=256, out_dtype=None, rows=None, ref=None, exact=False,
-                     fixup=sk.SK_FIXUP_FLAGS, launches=1, dp_first=False, k_aligned=True):
+                     fixup=sk.SK_FIXUP_FLAGS, launches=1, dp_first=False, k_aligned=True, variant=0):
     M, K = A.shape
     N = B.shape[1]
     print("case M=%d N=%d K=%d dtype=%d policy=%s blk=%s grid=%d out=%s fixup=%d dp_first=%d k_aligned=%d" %
           (M, N, K, dtype, sk.POLICY_NAMES[policy], blk, grid, out_dtype, fixup, dp_first, k_aligned), flush=True)
-    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup, dp_first=dp_first, k_aligned=k_aligned)
+    r = Runner(M, N, K, policy, blk, grid, dtype, out_dtype, fixup=fixup, dp_first=dp_first, k_aligned=k_aligned, variant=variant)
     try:
         # the library's schedule for this very launch equals the oracle's
         o = S.plan(M, N, K, policy, r.info["blk_m"], r.info["blk_n"], r.info["blk_k"], r.info["grid"], r.info["tile_order"],
@@ -76,14 +76,13 @@ def test_integer_inputs_bit_exact_every_tile_and_policy(blk, dtype):
 
 
 # wave layouts that are compiled in beside the default one of their tile (4 waves as 2 x 2; for the
-# 256 x 256 tile also 8 waves with two-stage rings), chosen with the environment variable SK_KERNEL_VARIANT
+# 256 x 256 tile also the 8-wave kernel with the coarser MAC loop), chosen with sk_plan_set_kernel_variant
 VARIANT_TILES = [(1, (256, 128, 64)), (1, (256, 256, 64)), (1, (128, 128, 64)), (1, (64, 128, 64)), (2, (256, 256, 64))]
 
 
 @pytest.mark.parametrize("variant,blk", VARIANT_TILES)
-def test_alternative_wave_layouts_integer_exact(variant, blk, monkeypatch):
-    monkeypatch.setenv("SK_KERNEL_VARIANT", str(variant))      # read by the library at every launch
-    r = Runner(512, 512, 512, sk.SK_POLICY_DP, blk, 24, inputs.BF16, sk.SK_F32)
+def test_alternative_wave_layouts_integer_exact(variant, blk):
+    r = Runner(512, 512, 512, sk.SK_POLICY_DP, blk, 24, inputs.BF16, sk.SK_F32, variant=variant)
     info = sk.sk_plan_kernel_info(r.plan)
     r.close()
     assert info["variant"] == variant and info["threads"] == (256 if variant == 1 else 512)
@@ -91,11 +90,11 @@ def test_alternative_wave_layouts_integer_exact(variant, blk, monkeypatch):
     A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 24)
     ref = G.gemm_fp64(A, B, G.BF16)
     for policy in range(8):
-        _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True)
+        _run_and_compare(A, B, inputs.BF16, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True, variant=variant)
     A, B = inputs.uniform_pair(M, N, K, inputs.F16, 25)        # 16-bit epilogue, aligned and unaligned rows
-    _run_and_compare(A, B, inputs.F16, sk.SK_POLICY_ALL_SK, blk, grid=24)
+    _run_and_compare(A, B, inputs.F16, sk.SK_POLICY_ALL_SK, blk, grid=24, variant=variant)
     A, B = inputs.uniform_pair(M + 3, N + 5, K + 1, inputs.BF16, 26)
-    _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_SK1_DP, blk, grid=24)
+    _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_SK1_DP, blk, grid=24, variant=variant)
 
 
 @pytest.mark.parametrize("shape", [(77, 101, 203), (1, 64, 16), (5, 7, 3), (130, 129, 1), (300, 8, 2049), (16, 264, 520)])

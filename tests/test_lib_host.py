@@ -177,22 +177,22 @@ def test_fixup_mode_setter_and_workspace_need():
     sk.sk_plan_destroy(p)
 
 
-def test_kernel_info_names_the_kernel_of_a_launch(monkeypatch):
+def test_kernel_info_names_the_kernel_of_a_launch():
     lib = sk.binding._lib
     assert lib.sk_plan_kernel_info(None, None, None, None) == sk.SK_ERR_INVALID_ARG
-    monkeypatch.delenv("SK_KERNEL_VARIANT", raising=False)
+    assert lib.sk_plan_set_kernel_variant(None, 1) == sk.SK_ERR_INVALID_ARG
     expect = {(256, 256, 64): 512, (256, 128, 64): 512, (128, 128, 64): 512, (64, 128, 64): 512, (32, 128, 64): 256, (16, 128, 64): 256}
     for blk, threads in expect.items():
         p = sk.sk_plan(1000, 1000, 1000, sk.SK_POLICY_ALL_SK, blk, 256, sk.SK_BF16)
         info = sk.sk_plan_kernel_info(p)
         assert info["variant"] == 0 and info["threads"] == threads and 0 < info["lds_bytes"] <= 160 * 1024
         assert lib.sk_plan_kernel_info(p, None, None, None) == sk.SK_OK
-        monkeypatch.setenv("SK_KERNEL_VARIANT", "1")               # a 4-wave layout where the tile has one
+        assert lib.sk_plan_set_kernel_variant(p, -1) == sk.SK_ERR_INVALID_ARG
+        sk.sk_plan_set_kernel_variant(p, 1)                        # a 4-wave layout where the tile has one
         alt = sk.sk_plan_kernel_info(p)
         assert (alt["variant"], alt["threads"]) == ((1, 256) if blk[0] >= 64 else (0, threads))
         sk.sk_plan_set_fixup(p, sk.SK_FIXUP_ATOMIC)                # the atomic set has no variants
         assert sk.sk_plan_kernel_info(p)["variant"] == 0
-        monkeypatch.delenv("SK_KERNEL_VARIANT")
         sk.sk_plan_destroy(p)
     p = sk.sk_plan(1000, 1000, 1000, sk.SK_POLICY_DP, (64, 64, 64), 256, sk.SK_BF16)   # a tile without a kernel
     assert lib.sk_plan_kernel_info(p, None, None, None) == sk.SK_ERR_UNSUPPORTED
