@@ -263,6 +263,26 @@ int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls);
  * tiles), WORKSPACE (plan has split tiles but no workspace), HIP (launch failed). */
 int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream);
 
+/* sk_gemm for callers that cannot allocate device memory or keep a workspace alive: code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as sk_gemm, but the flag lines and partial tiles live in an array inside
+ * the library's own device image (one copy per GPU that runs the library, held until the process
+ * ends) instead of caller-owned memory; whatever sk_plan_set_workspace attached to the plan is
+ * ignored.  The call allocates nothing and frees nothing.  Before the GEMM kernel it enqueues a small
+ * fill kernel that takes the flag and status lines down (the array keeps the previous call's
+ * contents), so a launch with split tiles is two kernels; a plan without split tiles is one.
+ * Limit: sk_workspace_bytes(plan) <= SK_STATIC_WORKSPACE_MAX_BYTES - enough for every tile shape on
+ * the default grid of 256 workgroups; larger grids with the largest tiles are refused.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may run at the same time
+ * (different streams, or replays of graphs that hold them) race on it; calls on one stream do not.
+ * A time-out of a tile owner (see sk_plan_set_spin_limit) cannot be read back through this entry
+ * point; the next call starts from cleared flags either way.  The first call on a device looks the
+ * array's address up and, like sk_gemm, sets up the kernel: make it outside graph capture.
+ * Errors: those of sk_gemm, plus WORKSPACE (the plan needs more than the limit) and UNSUPPORTED
+ * (SK_FIXUP_ATOMIC with a 16-bit output, whose fp32 image of D has no size bound). */
+#define SK_STATIC_WORKSPACE_MAX_BYTES ((size_t)257 * 128 + 384 + (size_t)256 * 256 * 256 * 4)
+int sk_gemm_static(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream);
+
 /* Blocking: waits for `stream` and reads the workspace status word.  Returns
  * SK_OK, or SK_ERR_TIMEOUT if any launch since the last check gave up waiting
  * for a partial tile; in that case the flag and status area is cleared, so the

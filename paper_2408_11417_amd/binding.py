@@ -34,7 +34,7 @@ SK_STREAMK_FIRST, SK_DATA_PARALLEL_FIRST = 0, 1
 SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
-           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_plan_set_kernel_variant", "sk_gemm", "sk_plan_check", "sk_plan_kernel_info",
+           "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_plan_set_kernel_variant", "sk_gemm", "sk_gemm_static", "sk_plan_check", "sk_plan_kernel_info",
            "sk_plan_destroy", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
@@ -89,6 +89,7 @@ _lib.sk_plan_set_batch_order.argtypes = [_vp, _int]
 _lib.sk_plan_set_segment_order.argtypes = [_vp, _int]
 _lib.sk_plan_estimate_us.argtypes = [_vp, ctypes.POINTER(ctypes.c_double)]
 _lib.sk_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.sk_gemm_static.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sk_plan_check.argtypes = [_vp, _vp]
 _lib.sk_plan_kernel_info.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int32)] * 3
 _lib.sk_plan_destroy.argtypes = [_vp]
@@ -208,6 +209,11 @@ def sk_plan_set_kernel_variant(plan, variant):
 def sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream=0):
     """Device pointers (ints) and a hipStream_t (int).  Asynchronous."""
     _check(_lib.sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream), "sk_gemm")
+
+
+def sk_gemm_static(A_ptr, B_ptr, D_ptr, plan, stream=0):
+    """sk_gemm with the workspace inside the library (no allocation anywhere on the call path)."""
+    _check(_lib.sk_gemm_static(A_ptr, B_ptr, D_ptr, plan, stream), "sk_gemm_static")
 
 
 def sk_gemm_bind(A_ptr, B_ptr, D_ptr, plan, stream=0):

@@ -102,7 +102,11 @@ extern "C" int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int3
     return SK_OK;
 }
 
-extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream) {
+namespace {
+
+// The launch behind sk_gemm and sk_gemm_static: `workspace` is the device memory that holds the flag
+// lines, the status line and the partial tiles (or the fp32 image of the atomic fix-up).
+int launch_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream, void* workspace) {
     if (!A || !B || !D || !plan) return SK_ERR_INVALID_ARG;
     const sk_plan_header& h = plan->h;
     const uintptr_t align = reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(D);
@@ -114,7 +118,7 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
     KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant);
     if (!e) return SK_ERR_UNSUPPORTED;
-    if (plan->needs_fixup && !plan->workspace && !(atomic && h.out_dtype == SK_F32)) return SK_ERR_WORKSPACE;
+    if (plan->needs_fixup && !workspace && !(atomic && h.out_dtype == SK_F32)) return SK_ERR_WORKSPACE;
     const bool aligned = (h.K % e->piece_elems == 0) && (h.N % e->piece_elems == 0);   // whole 16-byte pieces per row
     kernel_fn fn = aligned ? e->aligned : e->generic;
 
@@ -136,7 +140,7 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
 
     GemmArgs g{};
     g.A = A; g.B = B; g.D = D;
-    char* ws = static_cast<char*>(plan->workspace);
+    char* ws = static_cast<char*>(workspace);
     g.flags = reinterpret_cast<uint32_t*>(ws);
     g.status = ws ? reinterpret_cast<uint32_t*>(ws + sk_ws_status_offset(h.grid)) : nullptr;
     g.partials = ws ? reinterpret_cast<float*>(ws + sk_ws_partials_offset(h.grid)) : nullptr;
@@ -165,4 +169,63 @@ extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* p
     }
     hipLaunchKernelGGL(fn, dim3(h.grid), dim3(e->threads), e->lds_bytes, st, g);
     return hip_ok(hipGetLastError()) ? SK_OK : SK_ERR_HIP;
+}
+
+// ---- sk_gemm_static: the workspace lives in the library's own device image ---------------------
+// `scratch` is the workspace of every sk_gemm_static call on a device: flag lines, status line and
+// one fp32 partial tile per workgroup, in the layout of a caller-supplied workspace.  Each device
+// that loads the library holds its own copy until the process ends.  In host code the name of the
+// array is only a handle for hipGetSymbolAddress; the device address it yields (one per device) is
+// what kernels and fills get.
+constexpr size_t SK_STATIC_SCRATCH_BYTES = SK_STATIC_WORKSPACE_MAX;
+static_assert(SK_STATIC_SCRATCH_BYTES == SK_STATIC_WORKSPACE_MAX_BYTES, "the limit stated in streamk.h");
+static __device__ __align__(256) unsigned char scratch[SK_STATIC_SCRATCH_BYTES];
+
+constexpr int SK_MAX_DEVICES = 64;
+void* g_scratch_ptr[SK_MAX_DEVICES] = {};      // device address of `scratch` on device i, once asked for
+std::mutex g_scratch_mutex;
+
+// Flag and status lines back to zero (a fill kernel, not a memset node: the call may be captured into a graph).
+__global__ void clear_words_kernel(uint32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// Device address of this device's `scratch` (asked for once per device, with that device current).
+int static_scratch(void** out) {
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev))) return SK_ERR_HIP;
+    if (dev < 0 || dev >= SK_MAX_DEVICES) return SK_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return SK_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SK_OK;
+}
+
+}  // namespace
+
+extern "C" int sk_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream) {
+    if (!plan) return SK_ERR_INVALID_ARG;
+    return launch_gemm(A, B, D, plan, stream, plan->workspace);
+}
+
+extern "C" int sk_gemm_static(const void* A, const void* B, void* D, const sk_plan_t* plan, void* stream) {
+    if (!A || !B || !D || !plan) return SK_ERR_INVALID_ARG;
+    // the atomic fix-up accumulates into an fp32 image of D, whose size has no bound: caller-owned memory only
+    if (plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup && plan->h.out_dtype != SK_F32) return SK_ERR_UNSUPPORTED;
+    if (!plan->needs_fixup) return launch_gemm(A, B, D, plan, stream, nullptr);    // no split tile: nothing to exchange
+    if (sk_workspace_bytes(plan) > SK_STATIC_SCRATCH_BYTES) return SK_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != SK_OK) return rc;
+    // the array keeps what the last call left: a call that timed out may have left flags or the status up
+    const int words = (int)(sk_ws_partials_offset(plan->h.grid) / 4);
+    hipLaunchKernelGGL(clear_words_kernel, dim3((words + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t*>(ws), words);
+    if (!hip_ok(hipGetLastError())) return SK_ERR_HIP;
+    return launch_gemm(A, B, D, plan, stream, ws);
 }

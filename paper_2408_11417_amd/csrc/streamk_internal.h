@@ -23,6 +23,10 @@ constexpr int SK_TREE_GROUP = 8;   // contributors per group in the two-level re
 inline size_t sk_ws_status_offset(int grid) { return (size_t)grid * SK_FLAG_STRIDE; }
 inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_FLAG_STRIDE + 384; }
 
+// Size of the device array behind sk_gemm_static: the flag and status lines of 256 workgroups plus
+// 256 partial tiles of 256 x 256 fp32 (the largest tile), i.e. every plan on the default grid.
+constexpr size_t SK_STATIC_WORKSPACE_MAX = (256 + 1) * SK_FLAG_STRIDE + 384 + (size_t)256 * 256 * 256 * 4;
+
 // Does the GEMM launcher hold a kernel for this configuration?
 bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k);
 // Bytes of the fp32 image of D that the atomic fix-up accumulates into (0 if D itself serves).
