@@ -140,3 +140,18 @@ def sample_rows(M, n, seed):
     while len(rows) < n:
         rows.add(int(rng.integers(0, M)))
     return np.array(sorted(rows), dtype=np.int64)
+
+
+def sample_rows_per_band(M, band, per_band, seed):
+    """Seeded row indices that hit every band of `band` consecutive rows: in each band its first
+    row, one row of its second half and per_band - 2 random ones (all clipped to M), plus the
+    last row of the matrix."""
+    rng = np.random.default_rng(seed)
+    rows = {M - 1}
+    for b0 in range(0, M, band):
+        hi = min(b0 + band, M)
+        rows.add(b0)
+        rows.add(min(b0 + band // 2 + int(rng.integers(0, max(band // 2, 1))), hi - 1))
+        for _ in range(max(per_band - 2, 0)):
+            rows.add(int(rng.integers(b0, hi)))
+    return np.array(sorted(rows), dtype=np.int64)

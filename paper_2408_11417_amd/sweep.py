@@ -59,7 +59,12 @@ def time_policy(sk, torch, plan, sets, stream, est_ms, graph=False):
 
 
 def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, tile=None, dp_first=False, ascending=False, tile_order=None,
-        graph=False):
+        graph=False, verify=None):
+    """Time the seven policies on every shape; returns the records.  verify: optional callback
+    verify(record, policy, A, B, D) called for every shape after the timing, with the fastest policy
+    and host copies (numpy uint16 storage bits) of the operands of one launch of it and of its
+    result - the hook through which a test compares the very launches that were timed with a
+    reference of its own."""
     import torch
     import paper_2408_11417_amd as sk
 
@@ -131,12 +136,19 @@ def run(shapes, out_path, dtype_code=1, verbose=True, check_every=25, fixup=0, t
                "sk_tiles": [i["sk_tiles"] for i in infos], "time_ns": [int(round(t * 1e6)) for t in times],
                "reps": reps_used, "distinct_schedules": len(by_sched)}
         if check_every and idx % check_every == 0:
-            # consistency of the policies among themselves: all-Stream-K against data-parallel
+            # a log line, not a check: how far all-Stream-K and data-parallel results are apart (summation order only)
             sk.sk_gemm(dA, dB, pd.data_ptr(), plans[0], stream)
             sk.sk_gemm(dA, dB, pd2.data_ptr(), plans[6], stream)
             assert sk.sk_plan_check(plans[6], stream) == sk.SK_OK
             a, b = pd[:M * N].float(), pd2[:M * N].float()
             rec["dp_vs_allsk_maxdiff_over_rms"] = float((a - b).abs().max() / a.pow(2).mean().sqrt())
+        if verify is not None:
+            best = times.index(min(times))
+            pd[:M * N].zero_()
+            sk.sk_gemm(dA, dB, pd.data_ptr(), plans[best], stream)
+            assert sk.sk_plan_check(plans[best], stream) == sk.SK_OK
+            as_bits = lambda t, r, c: t[:r * c].view(torch.int16).cpu().numpy().view(np.uint16).reshape(r, c)
+            verify(rec, best, as_bits(pa, M, K), as_bits(pb, K, N), as_bits(pd, M, N))
         records.append(rec)
         for plan in plans:
             sk.sk_plan_destroy(plan)

@@ -164,12 +164,20 @@ def test_config3_skinny(M):
     _run_and_compare(c["A"], c["B"], inputs.BF16, sk.SK_POLICY_ALL_SK, None, 256, out_dtype=sk.SK_F32, ref=ref)
 
 
-def test_config5_large_square_bf16_sampled_rows():
-    c = inputs.config5(inputs.BF16)
-    rows = inputs.sample_rows(c["M"], 24, 5)
-    ref = G.gemm_fp64(c["A"], c["B"], G.BF16, rows=rows)
-    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK3_DP, sk.SK_POLICY_ALL_SK):
-        _run_and_compare(c["A"], c["B"], inputs.BF16, policy, None, 256, rows=rows, ref=ref)
+def _config5_all_policies(dtype):
+    # every one of the 32 tile rows (256 rows each) is sampled three times - its first row, a row in the
+    # lower wave's half, a random one - and every column of those rows is compared; all seven policies
+    c = inputs.config5(dtype)
+    rows = inputs.sample_rows_per_band(c["M"], 256, 3, 5 + dtype)
+    assert len(set(rows // 256)) == 32 and len(set(rows // 128)) >= 60
+    ref = G.gemm_fp64(c["A"], c["B"], ODT[dtype], rows=rows)
+    for policy in range(7):
+        _run_and_compare(c["A"], c["B"], dtype, policy, None, 256, rows=rows, ref=ref)
+    _run_and_compare(c["A"], c["B"], dtype, sk.SK_POLICY_SK3_DP, None, 256, out_dtype=sk.SK_F32, rows=rows, ref=ref)
+
+
+def test_config5_large_square_bf16_all_policies_every_tile_row():
+    _config5_all_policies(inputs.BF16)
 
 
 # ---- 8-bit (e4m3) inputs ---------------------------------------------------------------------------
@@ -208,12 +216,8 @@ def test_fp8_uniform_inputs_medium():
         _run_and_compare(A, B, inputs.E4M3, policy, None, 256, out_dtype=sk.SK_F32, ref=ref)
 
 
-def test_config5_large_square_fp8_sampled_rows():
-    c = inputs.config5(inputs.E4M3)
-    rows = inputs.sample_rows(c["M"], 24, 6)
-    ref = G.gemm_fp64(c["A"], c["B"], G.E4M3, rows=rows)
-    for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK3_DP, sk.SK_POLICY_ALL_SK):
-        _run_and_compare(c["A"], c["B"], inputs.E4M3, policy, None, 256, rows=rows, ref=ref)
+def test_config5_large_square_fp8_all_policies_every_tile_row():
+    _config5_all_policies(inputs.E4M3)
 
 
 # ---- atomic-add fix-up (the accumulation step of Algorithm 1): same schedules, partial tiles added into a zeroed fp32 image
@@ -401,10 +405,55 @@ def test_ascending_order_tiles_shared_by_many_workgroups(shape, blk, grid):
 
 def test_ascending_order_config2_rows_and_fp8():
     c = inputs.config2()
-    rows = inputs.sample_rows(c["M"], 24, 9)
+    rows = inputs.sample_rows_per_band(c["M"], 256, 3, 9)       # every one of the 15 tile rows, both wave halves
     ref = G.gemm_fp64(c["A"], c["B"], G.BF16, rows=rows)
     for policy in (1, 3, 6):
         _run_and_compare(c["A"], c["B"], inputs.BF16, policy, c["blk"], c["grid"], rows=rows, ref=ref, k_aligned=False)
     A, B = inputs.uniform_pair(1000, 1100, 2100, inputs.E4M3, 64)
     for policy in (1, 6):
         _run_and_compare(A, B, inputs.E4M3, policy, (256, 256, 128), 24, k_aligned=False)
+
+
+# ---- the tuning sweep and the Bloom selection on the device (Sec. 4.2, Sec. 5.1's profiler protocol) -----------
+
+def test_sweep_then_selector_on_first_sizes_and_two_skinny_ones(tmp_path):
+    """The sweep itself - not a sample of its sizes - on the first 16 sizes of the 500-size list plus two
+    skinny ones: every size is timed under the seven policies, the result of its fastest policy (one of
+    the launches the sweep makes) is compared with the oracle on sampled rows, and the records feed the
+    selector: no false negatives, the selected policy is a candidate (or the fall-back when the filters
+    know nothing), and it is never slower than every candidate."""
+    from paper_2408_11417_amd import sweep, selector
+    shapes = inputs.sweep_shapes(500, 4)[:16] + [(16, 8192, 8192), (64, 4096, 4096)]
+    checked = []
+
+    def verify(rec, policy, A, B, D):
+        M, N, K = rec["M"], rec["N"], rec["K"]
+        rows = inputs.sample_rows_per_band(M, rec["tile"][0], 2, M + K)[:24]
+        ref = G.gemm_fp64(A, B, G.BF16, rows=rows)
+        err = G.rel_error(G.decode_numpy(D[rows], G.BF16), ref)
+        print("sweep size %dx%dx%d tile %s best %s err %.2e" % (M, N, K, rec["tile"], sk.POLICY_NAMES[policy], err), flush=True)
+        assert err <= TOL_16
+        checked.append((M, N, K))
+
+    records = sweep.run(shapes, str(tmp_path / "sweep.json"), verbose=False, check_every=0, verify=verify)
+    assert checked == shapes and len(records) == len(shapes)
+    for r in records:
+        assert len(r["time_ns"]) == 7 and min(r["time_ns"]) > 0
+    split = 14
+    for mode in ("shape", "exact"):
+        out = selector.evaluate(records, split, 0.2, mode)
+        assert out["false_negatives"] == 0 and out["held_out_sizes"] == len(shapes) - split
+        assert 0.0 <= out["pruning_rate_build"] < 1.0
+    sel = selector.PolicySelector(records[:split], 0.2, "shape")
+    try:
+        for r in records:
+            p, mask, fell_back = sel.select(r, r["time_ns"])
+            cands = [q for q in range(7) if (mask >> q) & 1]
+            assert (p in cands) or (fell_back and not cands)
+            if cands:
+                assert r["time_ns"][p] == min(r["time_ns"][q] for q in cands)
+        for r in records[:split]:                      # every winner that was inserted comes back
+            want = selector.winner_mask(r["time_ns"], 0.2)
+            assert want & ~sel.candidates(r) == 0
+    finally:
+        sel.close()
