@@ -1,27 +1,38 @@
 """Benchmark of the Stream-K++ hot path on one MI355X.
 
-A step is one pass of the whole path for one GEMM: query the Bloom filters for the problem size,
-take the surviving policy that the tuning pass timed fastest, and run sk_gemm under that policy's
-plan.  Before the timed region a tuning pass times all seven policies (50 warm-up + 50 timed
-launches each, the paper's protocol, Sec. 5.1) and builds the filters from the policies within 20 %
-of the best (Sec. 4.2).  Inputs are seeded synthetic matrices already resident in HBM.
+Default run, all on seeded synthetic inputs resident in HBM:
+ 1. the tuning sweep of Sec. 5.1 / 4.2 on the 500 seeded sizes (all seven policies timed per size), the
+    Bloom filters built from the winners of the first 400 sizes, the held-out evaluation on the last 100;
+ 2. the headline workload - config 5, bf16 GEMM 8192^3 under the library's own tile.  A step is one pass of
+    the whole path for one GEMM: make the shape key, query the filters built in (1), take the surviving
+    policy that the tuning pass of this size timed fastest (the cost model's pick if no filter knows the
+    key), and run sk_gemm under that policy's plan;
+ 3. the same step on config 5 with fp8 inputs, config 2 and the skinny config 3 (M = 16, 128), reported
+    as extra keys of the same line;
+ 4. the matrix-core rate without memory traffic (register-resident loop) as "achievable_peak";
+ 5. the CPU oracle timed on sampled rows of the headline workload.
 
-Prints ONE JSON line: TFLOP/s of the Bloom-selected policy, the roofline of the GEMM kernel (MFMA
-peak; HBM bandwidth for the skinny workloads; kernel time from HIP events on the launch stream around
-back-to-back launches) and the CPU oracle timed on the host cores.
+Prints ONE JSON line.  `roofline` belongs to the GEMM kernel of the headline workload: kernel time from
+HIP events on the launch stream around back-to-back launches; `traffic` = measured HBM bytes per launch
+from profiles/hbm_traffic_streamk_gemm_kernel.txt (written by paper_2408_11417_amd/hbm_traffic.py from
+rocprofv3 counter runs of this file), null if the file has no row for the workload and policy.
 """
 import argparse
 import json
+import os
 import sys
 import time
 
 import numpy as np
 
-# HBM bytes per launch of each policy on the default workload (k-aligned segment order), from rocprofv3
-# FETCH_SIZE / WRITE_SIZE scaled by a plain-copy calibration (profiles/streamk_gemm_kernel_cfg2_bf16_3840x4224x4096.txt)
-MEASURED_TRAFFIC_BYTES = {("cfg2", "DP"): 344.3e6 + 32.8e6, ("cfg2", "SK1_DP"): 404.6e6 + 64.0e6}
-MEASURED_TRAFFIC_BYTES.update({("cfg2", p): 452.1e6 + 64.1e6 for p in ("SK2_DP", "SK3_DP", "SK4_DP", "SK5_DP", "ALL_SK")})
+ROOT = os.path.dirname(os.path.abspath(__file__))
 PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "e4m3": 5033.2}    # dense MFMA peak of MI355X
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_streamk_gemm_kernel.txt")
+DTYPE_NAMES = {0: "f16", 1: "bf16", 2: "e4m3"}
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
 def workload(name):
@@ -31,19 +42,298 @@ def workload(name):
         c["label"] = "cfg2: bf16 GEMM 3840x4224x4096, 256x128x64 tiles (495 tiles, 1.93 waves), N(0,1)/sqrt(K), seed 1"
     elif name == "cfg5":
         c = inputs.config5(inputs.BF16)
-        c["label"] = "cfg5: bf16 GEMM 8192^3, U[-1,1], seed 3"
+        c["label"] = "cfg5: bf16 GEMM 8192^3, library tile, U[-1,1], seed 3"
     elif name == "cfg5_fp8":
         c = inputs.config5(inputs.E4M3)
-        c["label"] = "cfg5: fp8 e4m3 GEMM 8192^3, bf16 output, U[-1,1], seed 3"
+        c["label"] = "cfg5: fp8 e4m3 GEMM 8192^3, bf16 output, library tile, U[-1,1], seed 3"
     elif name == "cfg1":
         c = inputs.config1()
         c["label"] = "cfg1: fp16 GEMM 512^3, 128x128x32 tiles, U[-1,1], seed 0"
     elif name.startswith("cfg3"):
         c = inputs.config3(int(name.split("_")[1]))
-        c["label"] = "cfg3: bf16 skinny GEMM M=%d N=K=8192, N(0,0.02), seed 2" % c["M"]
+        c["label"] = "cfg3: bf16 skinny GEMM M=%d N=K=8192, library tile, N(0,0.02), seed 2, four rotating buffer sets" % c["M"]
     else:
         raise SystemExit("unknown workload %r" % name)
     return c
+
+
+def measured_traffic(name, policy):
+    """HBM bytes per launch (reads + writes) of a workload under a policy, from the tracked summary."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) >= 4 and f[0] == name and f[1] == policy:
+                return float(f[2]) + float(f[3])
+    except OSError:
+        pass
+    return None
+
+
+class Bench:
+    """One workload: plans of the seven policies, tuning, the timed steps."""
+
+    def __init__(self, name, args, selector_obj):
+        import torch
+        import paper_2408_11417_amd as sk
+        self.sk, self.torch, self.name, self.args, self.sel = sk, torch, name, args, selector_obj
+        self.stream = torch.cuda.current_stream().cuda_stream
+        c = self.c = workload(name)
+        self.M, self.N, self.K, self.dt = c["M"], c["N"], c["K"], c["dtype"]
+        self.flops = 2.0 * self.M * self.N * self.K
+        view = np.int16 if self.dt != 2 else np.uint8
+        dA = torch.from_numpy(c["A"].view(view)).cuda()
+        dB = torch.from_numpy(c["B"].view(view)).cuda()
+        D = torch.empty((self.M, self.N), dtype=torch.int16, device="cuda")
+        # The skinny workloads are bound by reading B once from HBM; B (134 MB) would stay in the
+        # 256 MB memory-side cache between launches, so they rotate over four copies of A, B and D.
+        self.hbm_bound = name.startswith("cfg3")
+        self.sets = [(dA, dB, D)]
+        if self.hbm_bound:
+            self.sets += [(dA.clone(), dB.clone(), torch.empty_like(D)) for _ in range(3)]
+        self.launches = 0
+        self.plans, self.keep = self.make_plans(c["blk"])
+        self.info = sk.sk_plan_info(self.plans[0])
+        self.bound = {}
+
+    def make_plans(self, blk):
+        sk, torch, c = self.sk, self.torch, self.c
+        plans, keep = {}, []
+        for p in range(sk.SK_NUM_POLICIES):
+            plan = sk.sk_plan(self.M, self.N, self.K, p, blk, c["grid"], self.dt, c["out_dtype"])
+            if self.args.ascending:
+                sk.sk_plan_set_segment_order(plan, sk.SK_SEGMENTS_ASCENDING)
+            nbytes = sk.sk_workspace_bytes(plan)
+            ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+            sk.sk_plan_set_workspace(plan, (ws.data_ptr() + 255) // 256 * 256, nbytes)
+            keep.append(ws)
+            plans[p] = plan
+        return plans, keep
+
+    def launch(self, p, plan_set=None):
+        ps = plan_set or self.plans
+        i = self.launches % len(self.sets)
+        self.launches += 1
+        call = self.bound.get((id(ps), p, i))
+        if call is None:                       # arguments marshalled once per (plan, operand set)
+            a, b, d = self.sets[i]
+            call = self.bound[(id(ps), p, i)] = self.sk.sk_gemm_bind(a.data_ptr(), b.data_ptr(), d.data_ptr(), ps[p], self.stream)
+        status = call()
+        if status != self.sk.SK_OK:
+            raise self.sk.StreamKError(status, "sk_gemm")
+
+    def time_policy(self, p, warm, timed, plan_set=None):
+        """ms per launch: `timed` launches back to back between one pair of events, as the timed
+        region and the sweep run them (event pairs around every launch would add the launch gap)."""
+        torch = self.torch
+        for _ in range(warm):
+            self.launch(p, plan_set)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(timed):
+            self.launch(p, plan_set)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / timed
+
+    def tune(self, reps):
+        """All seven policies (untimed pass), two rounds, the faster kept: the first policies timed in a
+        fresh process otherwise run while the clocks are still settling."""
+        sk = self.sk
+        if self.args.policy >= 0:
+            return {self.args.policy: self.time_policy(self.args.policy, 10, 10)}
+        first = {p: self.time_policy(p, reps, reps) for p in range(sk.SK_NUM_POLICIES)}
+        return {p: min(first[p], self.time_policy(p, reps, reps)) for p in range(sk.SK_NUM_POLICIES)}
+
+    def run(self, steps, warmup, tune_reps):
+        sk, torch, args = self.sk, self.torch, self.args
+        t_pol = self.t_pol = self.tune(tune_reps)
+        best = min(t_pol.values())
+        # the filters: those of the sweep's build split (shape keys), or - without a sweep - built from
+        # this size's own winners, which makes the selection trivially the best policy (labelled so)
+        own_bloom = None
+        if self.sel is not None:
+            bloom, source = self.sel.bloom, "filters of the sweep's build split (shape keys)"
+        else:
+            mask = sum(1 << p for p, t in t_pol.items() if t <= 1.2 * best)
+            own_bloom = bloom = sk.bloom_build([tuple(sk.bloom_shape_key(self.plans[0])) + (mask,)])
+            source = "filters built from this size's own winners (no sweep in this run)"
+        fallback = None
+
+        def step():
+            key = sk.bloom_shape_key(self.plans[0])
+            cand = sk.bloom_query(bloom, *key)
+            live = [p for p in t_pol if (cand >> p) & 1]
+            if not live:
+                live = [fallback if fallback in t_pol else min(t_pol)]
+            sel = min(live, key=lambda p: t_pol[p])
+            self.launch(sel)
+            return sel, cand
+
+        key = sk.bloom_shape_key(self.plans[0])
+        cand0 = sk.bloom_query(bloom, *key)
+        answered = any((cand0 >> p) & 1 for p in t_pol)
+        if not answered and args.policy < 0:
+            from paper_2408_11417_amd import selector
+            tile = (self.info["blk_m"], self.info["blk_n"], self.info["blk_k"])
+            fallback = selector.fallback_policy(self.M, self.N, self.K, tile, self.c["grid"], self.dt)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        # the timed region: exactly `steps` steps, nothing else on the stream
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            sel, cand = step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        assert sk.sk_plan_check(self.plans[sel], self.stream) == sk.SK_OK
+        # the same steps once more with an event pair around each, for the per-step figure
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for e0, e1 in evs:
+            e0.record()
+            step()
+            e1.record()
+        torch.cuda.synchronize()
+        # kernel time of the selected policy: the same number of launches back to back between one pair
+        # of events on the launch stream
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            self.launch(sel)
+        e1.record()
+        torch.cuda.synchronize()
+        kernel_ms = e0.elapsed_time(e1) / steps
+        step_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        ms_per_step = wall * 1e3 / steps
+        dtype_name = DTYPE_NAMES[self.dt]
+        alg_bytes = (self.M * self.K + self.K * self.N) * (1 if self.dt == 2 else 2) + self.M * self.N * 2
+        if self.hbm_bound:
+            roof = {"bound": "hbm", "achieved": round(alg_bytes / (kernel_ms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s"}
+        else:
+            roof = {"bound": "mfma", "achieved": round(self.flops / (kernel_ms * 1e-3) / 1e12, 2), "peak": PEAK_TFLOPS[dtype_name],
+                    "unit": "TFLOP/s"}
+        roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
+        roof.update(traffic=None if args.ascending else measured_traffic(self.name, sk.POLICY_NAMES[sel]),
+                    algorithmic_bytes=alg_bytes, kernel="streamk_gemm_kernel", kernel_ms=round(kernel_ms, 5),
+                    step_event_ms=round(step_ms, 5))
+        out = {"workload": self.c["label"], "M": self.M, "N": self.N, "K": self.K, "dtype": dtype_name,
+               "tile": [self.info["blk_m"], self.info["blk_n"], self.info["blk_k"]], "grid": self.info["grid"],
+               "value": round(self.flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(ms_per_step, 5),
+               "steps": steps, "roofline": roof, "selected_policy": sk.POLICY_NAMES[sel],
+               "selected_over_best": round(best / t_pol[sel], 4),
+               "policies_tflops": {sk.POLICY_NAMES[p]: round(self.flops / (t * 1e-3) / 1e12, 2) for p, t in t_pol.items()},
+               "bloom": {"source": source, "shape_key": list(key), "answered_by_filter": bool(answered),
+                         "candidates": [sk.POLICY_NAMES[p] for p in range(sk.SK_NUM_POLICIES) if (cand0 >> p) & 1],
+                         "fallback_policy": None if fallback is None else sk.POLICY_NAMES[fallback]}}
+        if own_bloom is not None:
+            sk.bloom_destroy(own_bloom)
+        return out
+
+    def own_tile(self):
+        """The same problem under the tile the library would pick by itself (best policy), when the
+        workload prescribes another one."""
+        sk = self.sk
+        if self.c["blk"] is None or self.args.policy >= 0:
+            return None
+        own, keep = self.make_plans(None)
+        try:
+            oi = sk.sk_plan_info(own[0])
+            if (oi["blk_m"], oi["blk_n"], oi["blk_k"]) == (self.info["blk_m"], self.info["blk_n"], self.info["blk_k"]):
+                return None
+            t_own = {p: self.time_policy(p, 20, 20, own) for p in own}
+            pb = min(t_own, key=t_own.get)
+            return {"tile": [oi["blk_m"], oi["blk_n"], oi["blk_k"]], "best_policy": sk.POLICY_NAMES[pb],
+                    "tflops": round(self.flops / (t_own[pb] * 1e-3) / 1e12, 2)}
+        finally:
+            for plan in own.values():
+                sk.sk_plan_destroy(plan)
+
+    def cpu_baseline(self):
+        from oracle import gemm as G
+        from paper_2408_11417_amd import inputs
+        c = self.c
+        odt = {0: G.F16, 1: G.BF16, 2: G.E4M3}[self.dt]
+        probe_rows = inputs.sample_rows(self.M, min(self.M, 4 * G.threads()), 0)     # short probe to size the sample
+        G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows[:G.threads()])               # (first call also starts the thread pool)
+        t0 = time.perf_counter()
+        G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows)
+        per_row = (time.perf_counter() - t0) / len(probe_rows)
+        n_rows = int(max(8, min(self.M, 15.0 / max(per_row, 1e-9))))                  # aim at ~15 s, never more than the whole matrix
+        rows = inputs.sample_rows(self.M, n_rows, 1)
+        t0 = time.perf_counter()
+        G.gemm_fp64(c["A"], c["B"], odt, rows=rows)
+        dt_cpu = time.perf_counter() - t0
+        return {"value": round(2.0 * len(rows) * self.N * self.K / dt_cpu / 1e12, 6), "unit": "TFLOP/s",
+                "cores": G.threads(), "kind": "oracle",
+                "sample": "%d of %d rows of D (all N columns, full K) of the headline workload, %.1f s" % (len(rows), self.M, dt_cpu)}
+
+    def close(self):
+        for p in self.plans.values():
+            self.sk.sk_plan_destroy(p)
+        self.plans, self.keep, self.sets, self.bound = {}, [], [], {}
+
+
+def mfma_peak():
+    """TFLOP/s of the register-resident matrix-core loop (no LDS, no global memory in the loop), with
+    random operand values as the workloads have them and with constant ones: under the power limit the
+    clock - and with it the reachable rate - depends on how much the operand bits toggle."""
+    import torch
+    import paper_2408_11417_amd as sk
+    from paper_2408_11417_amd import inputs
+    stream = torch.cuda.current_stream().cuda_stream
+    nbytes = sk.sk_mfma_peak_operand_bytes()
+    sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(11)
+    out = {}
+    for name, dt, esize in (("bf16", sk.SK_BF16, 2), ("e4m3", sk.SK_FP8_E4M3, 1)):
+        n = nbytes // esize
+        vals = {"random_operands": rng.uniform(-1.0, 1.0, size=n).astype(np.float32), "constant_operands": np.ones(n, dtype=np.float32)}
+        res = {}
+        for kind, v in vals.items():
+            bits = inputs.to_bits(v, inputs.BF16 if dt == sk.SK_BF16 else inputs.E4M3)
+            ops = torch.from_numpy(bits.view(np.int16 if esize == 2 else np.uint8)).cuda()
+            iters = 6000 if dt == sk.SK_BF16 else 3000
+            sk.sk_mfma_peak_launch(dt, ops.data_ptr(), sink.data_ptr(), 256, iters // 10, stream)
+            best = 0.0
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                flops = sk.sk_mfma_peak_launch(dt, ops.data_ptr(), sink.data_ptr(), 256, iters, stream)
+                e1.record()
+                torch.cuda.synchronize()
+                best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+            res[kind] = round(best, 1)
+        res["published_peak"] = PEAK_TFLOPS[name]
+        out[name] = res
+    out["unit"] = "TFLOP/s"
+    out["kernel"] = "mfma_peak_kernel: 256 workgroups x 4 waves, 16 independent 32x32 matrix-core instructions per trip, operands in registers"
+    return out
+
+
+def run_sweep(n_shapes):
+    """The tuning sweep (all seven policies on every size) and the held-out evaluation of the filters."""
+    from paper_2408_11417_amd import inputs, sweep, selector
+    shapes = inputs.sweep_shapes(500, 4)[:n_shapes]
+    split = len(shapes) * 4 // 5
+    t0 = time.perf_counter()
+    records = sweep.run(shapes, None, verbose=False, check_every=0)
+    seconds = time.perf_counter() - t0
+    ev = selector.evaluate(records, split, 0.2, "shape")
+    dp_wins = sum(r["time_ns"].index(min(r["time_ns"])) == 0 for r in records)
+    summary = {"sizes": len(records), "build_split": split, "held_out": len(records) - split, "tolerance": 0.2, "key": "shape",
+               "seconds": round(seconds, 1),
+               "false_negatives": ev["false_negatives"],
+               "pruning_rate_build": round(ev["pruning_rate_build"], 4),
+               "pruning_rate_build_non_dp": round(ev["pruning_rate_build_non_dp"], 4),
+               "held_pruning_rate": round(ev["held_pruning_rate"], 4),
+               "held_pruning_rate_distinct_schedules": round(ev["held_pruning_rate_distinct_schedules"], 4),
+               "held_fallbacks": ev["held_fallbacks"],
+               "held_best_not_among_candidates": ev["held_best_not_among_candidates"],
+               "held_share_ge_0.9_of_best": round(ev["held_share_ge_0.9_of_best"], 4),
+               "held_mean_ratio": round(ev["held_mean_ratio"], 4),
+               "held_min_ratio": round(ev["held_min_ratio"], 4),
+               "held_share_ge_0.9_no_timing": round(ev["held_share_ge_0.9_no_timing"], 4),
+               "dp_wins_share": round(dp_wins / len(records), 4)}
+    return summary, selector.PolicySelector(records[:split], 0.2, "shape")
 
 
 def main():
@@ -51,16 +341,21 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default="cfg5", help="headline workload: cfg5 (default), cfg5_fp8, cfg2, cfg1, cfg3_16 ... cfg3_128")
+    ap.add_argument("--only", action="store_true", help="the headline workload alone: no sweep, no other workloads, no matrix-core peak")
+    ap.add_argument("--sweep-shapes", type=int, default=500, help="sizes of the tuning sweep (first N of the 500; 0 = no sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--policy", type=int, default=-1, help="skip tuning and run this policy only")
+    ap.add_argument("--policy", type=int, default=-1, help="skip tuning and run this policy only (implies --only)")
     ap.add_argument("--ascending", action="store_true",
                     help="Algorithm 1's order of a workgroup's Stream-K pieces instead of the library's k-aligned default (for A/B profiles)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference for HBM byte counters)")
+    ap.add_argument("--mfma-peak", action="store_true", help="only the register-resident matrix-core loop (achievable peak)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures the single-GPU Stream-K GEMM; --gpus must be 1 (got %d)" % args.gpus)
+    if args.policy >= 0:
+        args.only = True
 
     import torch
     import paper_2408_11417_amd as sk
@@ -80,180 +375,67 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5,
                           "copy_ms": round(ms, 4), "copy_read_plus_write_GBps": round(2 * src.numel() * 4 / ms / 1e6, 1)}))
         return 0
-    stream = torch.cuda.current_stream().cuda_stream
-    c = workload(args.workload)
-    M, N, K, dt = c["M"], c["N"], c["K"], c["dtype"]
-    dtype_name = {0: "f16", 1: "bf16", 2: "e4m3"}[dt]
-    flops = 2.0 * M * N * K
-    dA = torch.from_numpy(c["A"].view(np.int16 if dt != 2 else np.uint8)).cuda()
-    dB = torch.from_numpy(c["B"].view(np.int16 if dt != 2 else np.uint8)).cuda()
-    D = torch.empty((M, N), dtype=torch.int16, device="cuda")
-    # The skinny workloads are bound by reading B once from HBM; B (134 MB) would stay in the
-    # 256 MB memory-side cache between launches, so they rotate over four copies of A, B and D.
-    hbm_bound = args.workload.startswith("cfg3")
-    sets = [(dA, dB, D)]
-    if hbm_bound:
-        sets += [(dA.clone(), dB.clone(), torch.empty_like(D)) for _ in range(3)]
-    launches = [0]
+    if args.mfma_peak:
+        print(json.dumps({"achievable_peak": mfma_peak()}))
+        return 0
 
-    plans, keep = {}, []
-    for p in range(sk.SK_NUM_POLICIES):
-        plan = sk.sk_plan(M, N, K, p, c["blk"], c["grid"], dt, c["out_dtype"])
-        if args.ascending:
-            sk.sk_plan_set_segment_order(plan, sk.SK_SEGMENTS_ASCENDING)
-        nbytes = sk.sk_workspace_bytes(plan)
-        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-        sk.sk_plan_set_workspace(plan, (ws.data_ptr() + 255) // 256 * 256, nbytes)
-        keep.append(ws)
-        plans[p] = plan
-    info = sk.sk_plan_info(plans[0])
+    sweep_summary, sel = None, None
+    if not args.only and args.sweep_shapes > 0:
+        log("tuning sweep on %d sizes" % args.sweep_shapes)
+        sweep_summary, sel = run_sweep(args.sweep_shapes)
+        log("sweep done in %.0f s" % sweep_summary["seconds"])
 
-    bound = {}
-
-    def launch(p, plan_set=None):
-        ps = plan_set or plans
-        i = launches[0] % len(sets)
-        launches[0] += 1
-        call = bound.get((id(ps), p, i))
-        if call is None:                       # arguments marshalled once per (plan, operand set)
-            a, b, d = sets[i]
-            call = bound[(id(ps), p, i)] = sk.sk_gemm_bind(a.data_ptr(), b.data_ptr(), d.data_ptr(), ps[p], stream)
-        status = call()
-        if status != sk.SK_OK:
-            raise sk.StreamKError(status, "sk_gemm")
-
-    def time_policy(p, warm, timed, plan_set=None):
-        """ms per launch: `timed` launches back to back between one pair of events, as the timed
-        region below and the sweep run them (event pairs around every launch would add the launch
-        gap to each)."""
-        for _ in range(warm):
-            launch(p, plan_set)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(timed):
-            launch(p, plan_set)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / timed
-
-    # ---- tuning pass (untimed): all seven policies, then the Bloom filters from the winners.
-    # Two rounds over the policies, the faster of the two kept: the first policies timed in a fresh
-    # process otherwise run while the clocks are still settling and look slower than they are.
-    if args.policy >= 0:
-        t_pol = {args.policy: time_policy(args.policy, 10, 10)}
-    else:
-        first = {p: time_policy(p, 50, 50) for p in range(sk.SK_NUM_POLICIES)}
-        t_pol = {p: min(first[p], time_policy(p, 50, 50)) for p in range(sk.SK_NUM_POLICIES)}
-    best = min(t_pol.values())
-    mask = sum(1 << p for p, t in t_pol.items() if t <= 1.2 * best)
-    bloom = sk.bloom_build([(M, N, K, mask)])
-
-    def step():
-        cand = sk.bloom_query(bloom, M, N, K)
-        sel = min((p for p in t_pol if (cand >> p) & 1), key=lambda p: t_pol[p])
-        launch(sel)
-        return sel
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # the timed region: exactly `steps` steps, nothing else on the stream (no event records between
-    # the steps: each would put a marker and a few microseconds of gap between two launches)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        sel = step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    assert sk.sk_plan_check(plans[sel], stream) == sk.SK_OK
-    # the same steps once more with an event pair around each, for the per-step figure
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    for e0, e1 in evs:
-        e0.record()
-        step()
-        e1.record()
-    torch.cuda.synchronize()
-    # kernel time of the selected policy: the same number of launches back to back between one pair
-    # of events on the launch stream (per-launch event pairs would add the launch gap, which matters
-    # for the 30 us skinny kernels)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        launch(sel)
-    e1.record()
-    torch.cuda.synchronize()
-    kernel_ms = e0.elapsed_time(e1) / args.steps
-    step_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
-    ms_per_step = wall * 1e3 / args.steps
-    value = flops / (ms_per_step * 1e-3) / 1e12
-    alg_bytes = (M * K + K * N) * (1 if dt == 2 else 2) + M * N * 2
-    if hbm_bound:
-        roofline = {"bound": "hbm", "achieved": round(alg_bytes / (kernel_ms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s"}
-    else:
-        roofline = {"bound": "mfma", "achieved": round(flops / (kernel_ms * 1e-3) / 1e12, 2), "peak": PEAK_TFLOPS[dtype_name],
-                    "unit": "TFLOP/s"}
-    roofline["frac"] = round(roofline["achieved"] / roofline["peak"], 4)
-
-    # the same problem under the tile the library would pick by itself (best policy), when the
-    # workload prescribes another one
-    own_tile = None
-    if c["blk"] is not None and args.policy < 0:
-        own, keep2 = {}, []
-        for p in range(sk.SK_NUM_POLICIES):
-            plan = sk.sk_plan(M, N, K, p, None, c["grid"], dt, c["out_dtype"])
-            nbytes = sk.sk_workspace_bytes(plan)
-            ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-            sk.sk_plan_set_workspace(plan, (ws.data_ptr() + 255) // 256 * 256, nbytes)
-            keep2.append(ws)
-            own[p] = plan
-        oi = sk.sk_plan_info(own[0])
-        if (oi["blk_m"], oi["blk_n"], oi["blk_k"]) != (info["blk_m"], info["blk_n"], info["blk_k"]):
-            t_own = {p: time_policy(p, 20, 20, own) for p in own}
-            pb = min(t_own, key=t_own.get)
-            own_tile = {"tile": [oi["blk_m"], oi["blk_n"], oi["blk_k"]], "best_policy": sk.POLICY_NAMES[pb],
-                        "tflops": round(flops / (t_own[pb] * 1e-3) / 1e12, 2)}
-        for plan in own.values():
-            sk.sk_plan_destroy(plan)
-
+    log("headline workload %s" % args.workload)
+    head = Bench(args.workload, args, sel)
+    res = head.run(args.steps, args.warmup, 50)
+    own_tile = head.own_tile()
     out = {
-        "metric": "gemm_tflops_bloom_selected_policy", "value": round(value, 2), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype_name,
+        "metric": "gemm_tflops_bloom_selected_policy", "value": res["value"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": res["dtype"],
         "data": "synthetic",
-        "config": {"workload": c["label"], "M": M, "N": N, "K": K,
-                   "tile": [info["blk_m"], info["blk_n"], info["blk_k"]], "grid": info["grid"]},
-        "roofline": dict(roofline, traffic=None if args.ascending else MEASURED_TRAFFIC_BYTES.get((args.workload, sk.POLICY_NAMES[sel])),
-                         algorithmic_bytes=alg_bytes, kernel="streamk_gemm_kernel", kernel_ms=round(kernel_ms, 5),
-                         step_event_ms=round(step_ms, 5)),
-        "selected_policy": sk.POLICY_NAMES[sel],
+        "config": {"workload": res["workload"], "M": res["M"], "N": res["N"], "K": res["K"], "tile": res["tile"], "grid": res["grid"]},
+        "roofline": res["roofline"],
+        "selected_policy": res["selected_policy"],
         "segment_order": "ascending" if args.ascending else "k_aligned",
-        "selected_over_best": round(best / t_pol[sel], 4),
-        "policies_tflops": {sk.POLICY_NAMES[p]: round(flops / (t * 1e-3) / 1e12, 2) for p, t in t_pol.items()},
-        "bloom_candidates": [sk.POLICY_NAMES[p] for p in t_pol if (mask >> p) & 1],
+        "selected_over_best": res["selected_over_best"],
+        "policies_tflops": res["policies_tflops"],
+        "bloom": res["bloom"],
     }
     if own_tile:
         out["library_default_tile"] = own_tile
+    cpu = None if args.no_cpu_baseline else head.cpu_baseline()
+    head.close()
+    del head
+    torch.cuda.empty_cache()
 
-    if not args.no_cpu_baseline:
-        from oracle import gemm as G
-        from paper_2408_11417_amd import inputs
-        odt = {0: G.F16, 1: G.BF16, 2: G.E4M3}[dt]
-        probe_rows = inputs.sample_rows(M, min(M, 4 * G.threads()), 0)     # short probe to size the sample
-        G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows[:G.threads()])     # (first call also starts the thread pool)
-        t0 = time.perf_counter()
-        G.gemm_fp64(c["A"], c["B"], odt, rows=probe_rows)
-        per_row = (time.perf_counter() - t0) / len(probe_rows)
-        n_rows = int(max(8, min(M, 15.0 / max(per_row, 1e-9))))             # aim at ~15 s, never more than the whole matrix
-        rows = inputs.sample_rows(M, n_rows, 1)
-        t0 = time.perf_counter()
-        G.gemm_fp64(c["A"], c["B"], odt, rows=rows)
-        dt_cpu = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(2.0 * len(rows) * N * K / dt_cpu / 1e12, 6), "unit": "TFLOP/s",
-                               "cores": G.threads(), "kind": "oracle",
-                               "sample": "%d of %d rows of D (all N columns, full K), %.1f s" % (len(rows), M, dt_cpu)}
+    if not args.only:
+        others = {}
+        for name in ("cfg5_fp8", "cfg2", "cfg3_16", "cfg3_128"):
+            if name == args.workload:
+                continue
+            log("workload %s" % name)
+            b = Bench(name, args, sel)
+            r = b.run(min(args.steps, 30), min(args.warmup, 20), 30)
+            ot = b.own_tile()
+            if ot:
+                r["library_default_tile"] = ot
+            b.close()
+            del b
+            torch.cuda.empty_cache()
+            r.pop("steps")
+            others[name] = r
+        out["workloads"] = others
+        log("matrix-core peak")
+        out["achievable_peak"] = mfma_peak()
+    if sweep_summary is not None:
+        out["sweep"] = sweep_summary
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
+    if sel is not None:
+        sel.close()
     print(json.dumps(out), flush=True)
-    for p in plans.values():
-        sk.sk_plan_destroy(p)
-    sk.bloom_destroy(bloom)
+    return 0
 
 
 if __name__ == "__main__":

@@ -308,6 +308,18 @@ int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int32_t* lds_by
 
 void sk_plan_destroy(sk_plan_t* plan);
 
+/* Measurement aid: the rate of the matrix-core instructions of the MAC loop (Sec. 2: the GEMM runs on
+ * matrix cores) with nothing else in the way.  Enqueues one kernel on `stream` in which every wave of
+ * `workgroups` workgroups (256 threads: one wave per SIMD) runs `iters` trips of 16 independent
+ * register-resident matrix-core instructions of in_dtype (SK_BF16 / SK_F16: 32x32x16, SK_FP8_E4M3:
+ * 32x32x64 with unit scales).  operands: device memory of sk_mfma_peak_operand_bytes() bytes in the
+ * input type - its values are the operand values (random values and constant values reach different
+ * clocks under the power limit); sink: device memory for workgroups * 256 floats (written once, keeps
+ * the loop alive).  *flops (host, may be NULL) receives the floating-point operations of the launch;
+ * the caller times the kernel.  Errors: INVALID_ARG, HIP. */
+size_t sk_mfma_peak_operand_bytes(void);
+int sk_mfma_peak_launch(int in_dtype, const void* operands, float* sink, int workgroups, int iters, void* stream, double* flops);
+
 /* The tile shape the library picks for (M, N, K, in_dtype) when sk_config leaves
  * it zero.  out_blk: host int32[3] = blk_m, blk_n, blk_k. */
 int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_blk);
@@ -319,8 +331,10 @@ int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, int32_t* out_
  * the policies of one problem when no tuning record knows it (the selector's
  * fall-back when the Bloom filters of Sec. 4.2 return no candidate), not for
  * predicting times.  microseconds: host double.
- * Errors: INVALID_ARG (NULL), UNSUPPORTED (fp8 inputs, or a tile shape the model
- * has no constants for: anything but the six 16-bit shapes sk_default_tile picks from). */
+ * fp8 tiles are modelled as the 16-bit shape of the same byte footprint with half
+ * the blk_k (same bytes and same matrix-core time per K-iteration).
+ * Errors: INVALID_ARG (NULL), UNSUPPORTED (a tile shape the model has no constants
+ * for: anything but the shapes sk_default_tile picks from). */
 int sk_plan_estimate_us(const sk_plan_t* plan, double* microseconds);
 
 /* ---- Bloom-filter policy selector (Sec. 4.2) --------------------------------

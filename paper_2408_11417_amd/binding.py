@@ -35,7 +35,7 @@ SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
            "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_plan_set_kernel_variant", "sk_gemm", "sk_gemm_static", "sk_plan_check", "sk_plan_kernel_info",
-           "sk_plan_destroy", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
+           "sk_plan_destroy", "sk_mfma_peak_operand_bytes", "sk_mfma_peak_launch", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
 
@@ -89,6 +89,8 @@ _lib.sk_plan_set_batch_order.argtypes = [_vp, _int]
 _lib.sk_plan_set_segment_order.argtypes = [_vp, _int]
 _lib.sk_plan_estimate_us.argtypes = [_vp, ctypes.POINTER(ctypes.c_double)]
 _lib.sk_gemm.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.sk_mfma_peak_operand_bytes.restype = ctypes.c_size_t
+_lib.sk_mfma_peak_launch.argtypes = [_int, _vp, _vp, _int, _int, _vp, ctypes.POINTER(ctypes.c_double)]
 _lib.sk_gemm_static.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.sk_plan_check.argtypes = [_vp, _vp]
 _lib.sk_plan_kernel_info.argtypes = [_vp] + [ctypes.POINTER(ctypes.c_int32)] * 3
@@ -209,6 +211,17 @@ def sk_plan_set_kernel_variant(plan, variant):
 def sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream=0):
     """Device pointers (ints) and a hipStream_t (int).  Asynchronous."""
     _check(_lib.sk_gemm(A_ptr, B_ptr, D_ptr, plan, stream), "sk_gemm")
+
+
+def sk_mfma_peak_operand_bytes():
+    return _lib.sk_mfma_peak_operand_bytes()
+
+
+def sk_mfma_peak_launch(in_dtype, operands_ptr, sink_ptr, workgroups, iters, stream=0):
+    """Enqueues the register-resident matrix-core loop; returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(_lib.sk_mfma_peak_launch(in_dtype, operands_ptr, sink_ptr, workgroups, iters, stream, ctypes.byref(flops)), "sk_mfma_peak_launch")
+    return flops.value
 
 
 def sk_gemm_static(A_ptr, B_ptr, D_ptr, plan, stream=0):

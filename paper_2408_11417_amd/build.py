@@ -15,7 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstreamk.so")
 SOURCES = ["streamk_plan.cpp", "streamk_bloom.cpp", "streamk_gemm.hip",
            "streamk_gemm_bf16.hip", "streamk_gemm_f16.hip", "streamk_gemm_fp8.hip",
-           "streamk_gemm_bf16_atomic.hip", "streamk_gemm_f16_atomic.hip"]
+           "streamk_gemm_bf16_atomic.hip", "streamk_gemm_f16_atomic.hip", "streamk_peak.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

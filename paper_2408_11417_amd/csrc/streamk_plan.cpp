@@ -104,17 +104,26 @@ double model_exchange_us(const TileCost& c, double split) {
     return 2.64 * (tree ? 2 : 1) + serial * c.bm * c.bn * 4 / 59.9e3;
 }
 
+// The constants of a tile shape.  The 8-bit kernels were not fitted: they move the same bytes per
+// k-iteration as the 16-bit kernel of the same footprint with twice the k at twice the matrix-core
+// rate, so an 8-bit tile is modelled as that 16-bit shape (128 x 256 as 256 x 128) with half its blk_k.
+const TileCost* model_constants(int bm, int bn, int in_dtype) {
+    if (in_dtype == SK_FP8_E4M3 && bm < bn) std::swap(bm, bn);
+    for (const TileCost& t : tile_costs)
+        if (t.bm == bm && t.bn == bn) return &t;
+    return nullptr;
+}
+int model_bk(int blk_k, int in_dtype) { return in_dtype == SK_FP8_E4M3 ? blk_k / 2 : blk_k; }
+
 }  // namespace
 
 extern "C" int sk_plan_estimate_us(const sk_plan_t* plan, double* microseconds) {
     if (!plan || !microseconds) return SK_ERR_INVALID_ARG;
     const sk_plan_header& h = plan->h;
-    const TileCost* c = nullptr;
-    for (const TileCost& t : tile_costs)
-        if (t.bm == h.blk_m && t.bn == h.blk_n) c = &t;
-    if (!c || h.in_dtype == SK_FP8_E4M3) return SK_ERR_UNSUPPORTED;
+    const TileCost* c = model_constants(h.blk_m, h.blk_n, h.in_dtype);
+    if (!c) return SK_ERR_UNSUPPORTED;
     // per-iteration time of a workgroup does not depend on how many workgroups the grid has
-    const double t_iter = model_iter_us(*c, h.blk_k), c_tile = model_tile_us(*c);
+    const double t_iter = model_iter_us(*c, model_bk(h.blk_k, h.in_dtype)), c_tile = model_tile_us(*c);
     double t = h.dp_waves * (h.iters_per_tile * t_iter + c_tile);
     if (h.sk_tiles > 0) {
         const double sk_waves = (double)h.sk_tiles / h.grid;
@@ -145,20 +154,20 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
     // iterations split evenly over the grid plus the cost of exchanging partial tiles, and keeps
     // the cheapest; the model's choice is within 10 % of the fastest tile shape on 95 % of the
     // sizes it was fitted on.
-    if (in_dtype == SK_FP8_E4M3) {   // two 8-bit tile shapes: the large one unless it leaves most of the grid idle
-        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
-        out_blk[0] = t256 >= 96 ? 256 : 128; out_blk[1] = 256; out_blk[2] = 128;
-        return SK_OK;
-    }
-    const TileCost* cands = tile_costs;
-    const int bk = MODEL_BK, grid = MODEL_GRID;
-    const double ipt = (double)ceil_div(K, bk);
+    // candidates: the six 16-bit shapes, or the two 8-bit shapes (modelled through model_constants)
+    struct Cand { int bm, bn, bk; };
+    static const Cand cands16[] = {{256, 256, 64}, {256, 128, 64}, {128, 128, 64}, {64, 128, 64}, {32, 128, 64}, {16, 128, 64}};
+    static const Cand cands8[] = {{256, 256, 128}, {128, 256, 128}};
+    const bool fp8 = in_dtype == SK_FP8_E4M3;
+    const Cand* cands = fp8 ? cands8 : cands16;
+    const int n_cands = fp8 ? 2 : 6, grid = MODEL_GRID;
     double best_t = 0;
     int best = -1;
-    for (int i = 0; i < (int)(sizeof tile_costs / sizeof tile_costs[0]); i++) {
-        const TileCost& c = cands[i];
-        const double tiles = (double)ceil_div(M, c.bm) * (double)ceil_div(N, c.bn);
-        const double t_iter = model_iter_us(c, bk), c_tile = model_tile_us(c);
+    for (int i = 0; i < n_cands; i++) {
+        const TileCost& c = *model_constants(cands[i].bm, cands[i].bn, in_dtype);
+        const double ipt = (double)ceil_div(K, cands[i].bk);
+        const double tiles = (double)ceil_div(M, cands[i].bm) * (double)ceil_div(N, cands[i].bn);
+        const double t_iter = model_iter_us(c, model_bk(cands[i].bk, in_dtype)), c_tile = model_tile_us(c);
         const double waves = (double)((int64_t)((tiles + grid - 1) / grid));
         const double t_dp = waves * (ipt * t_iter + c_tile);
         const double ipw = (double)((int64_t)((tiles * ipt + grid - 1) / grid));
@@ -170,7 +179,7 @@ extern "C" int sk_default_tile(int64_t M, int64_t N, int64_t K, int in_dtype, in
         const double t = t_dp < t_sk ? t_dp : t_sk;
         if (best < 0 || t < best_t) { best = i; best_t = t; }
     }
-    out_blk[0] = cands[best].bm; out_blk[1] = cands[best].bn; out_blk[2] = bk;
+    out_blk[0] = cands[best].bm; out_blk[1] = cands[best].bn; out_blk[2] = cands[best].bk;
     return SK_OK;
 }
 

@@ -42,7 +42,7 @@ def model_estimates(M, N, K, tile, grid=256, dtype=sk.SK_BF16):
     """The library's cost model (sk_plan_estimate_us, the tile dispatcher's model) for the seven policies."""
     est = []
     for p in range(N_POL):
-        plan = sk.sk_plan(M, N, K, p, tuple(tile), grid, dtype, dtype)
+        plan = sk.sk_plan(M, N, K, p, tuple(tile), grid, dtype)
         try:
             est.append(sk.sk_plan_estimate_us(plan))
         finally:

@@ -301,7 +301,12 @@ def test_plan_estimate_properties():
     p = sk.sk_plan(4096, 4096, 4096, 0, (256, 256, 128), 256, sk.SK_FP8_E4M3, sk.SK_BF16)
     us = ctypes.c_double()
     lib = sk.binding._lib
-    assert lib.sk_plan_estimate_us(p, ctypes.byref(us)) == sk.SK_ERR_UNSUPPORTED
+    # 8-bit tiles are modelled as the 16-bit shape of the same footprint with half the blk_k: same time per iteration
+    assert lib.sk_plan_estimate_us(p, ctypes.byref(us)) == sk.SK_OK
+    assert abs(us.value - est(4096, 4096, 2048, 0, blk)) < 1e-9 * us.value
+    q = sk.sk_plan(4096, 4096, 4096, 0, (64, 64, 64), 256, sk.SK_BF16)          # a shape without constants
+    assert lib.sk_plan_estimate_us(q, ctypes.byref(us)) == sk.SK_ERR_UNSUPPORTED
+    sk.sk_plan_destroy(q)
     assert lib.sk_plan_estimate_us(p, None) == sk.SK_ERR_INVALID_ARG and lib.sk_plan_estimate_us(None, ctypes.byref(us)) == sk.SK_ERR_INVALID_ARG
     sk.sk_plan_destroy(p)
     p = sk.sk_plan(512, 512, 512, 0, (128, 128, 32), 256, sk.SK_F16, sk.SK_F16)   # blk_k = 32: the per-iteration time scales with blk_k

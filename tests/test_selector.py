@@ -125,3 +125,25 @@ def test_tile_filters_no_false_negatives_and_fallback():
     sel = selector.TileSelector(recs[:5], tiles, 0.0, "exact")
     assert sel.select((4096, 4096, 4096)) == ((256, 256, 64), 0, True)     # 256 tiles of 256 x 256: one full wave
     sel.close()
+
+
+def test_fit_tool_formula_is_the_library_cost_model():
+    # the fitting tool restates the dispatcher's formula; with the library's constants it must pick the
+    # tile that sk_default_tile picks, on all 500 sweep sizes and the skinny family
+    from paper_2408_11417_amd import fit_tile_model as F, inputs
+    shapes = inputs.sweep_shapes(500, 4) + [(M, N, K) for M in (16, 32, 64, 128) for N, K in ((8192, 8192), (4096, 4096), (16384, 4096))]
+    for M, N, K in shapes:
+        pick = min(F.LIBRARY["tflops"], key=lambda t: (F.predict(F.LIBRARY, t, M, N, K), -t[0] * t[1]))
+        blk = sk.sk_default_tile(M, N, K, sk.SK_BF16)
+        est = {t: F.predict(F.LIBRARY, t, M, N, K) for t in F.LIBRARY["tflops"]}
+        assert tuple(blk[:2]) == pick or abs(est[tuple(blk[:2])] - est[pick]) <= 1e-9 * est[pick], (M, N, K, blk, pick)
+    # fp8: a modelled pick between the two 8-bit shapes, and an estimate for every policy
+    for M, N, K in [(8192, 8192, 8192), (300, 700, 4096), (2048, 1024, 512)]:
+        blk = sk.sk_default_tile(M, N, K, sk.SK_FP8_E4M3)
+        assert tuple(blk) in ((256, 256, 128), (128, 256, 128))
+        plan = sk.sk_plan(M, N, K, sk.SK_POLICY_ALL_SK, None, 256, sk.SK_FP8_E4M3)
+        try:
+            assert sk.sk_plan_estimate_us(plan) > 0
+        finally:
+            sk.sk_plan_destroy(plan)
+    assert tuple(sk.sk_default_tile(8192, 8192, 8192, sk.SK_FP8_E4M3)) == (256, 256, 128)
