@@ -678,6 +678,7 @@ __device__ __forceinline__ void add_block_partials(typename Mfma<C::DT, C::MF>::
 #pragma unroll
             for (int r = 0; r < C::ACC; r++)
                 v[j][r] = __hip_atomic_load(src + j * stride + r * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_sched_barrier(0);     // all loads of the round trip in flight before the first addition waits for one
 #pragma unroll
         for (int j = 0; j < GB; j++)
 #pragma unroll
@@ -717,6 +718,7 @@ __device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&
 #pragma unroll
             for (int i = 0; i < C::ACC_REGS; i++)
                 v[j][i] = __hip_atomic_load(p + j * stride + i * C::THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_sched_barrier(0);     // all loads of the round trip in flight before the first addition waits for one
 #pragma unroll
         for (int j = 0; j < CNT; j++)
 #pragma unroll
