@@ -293,10 +293,13 @@ int sk_gemm_static(const void* A, const void* B, void* D, const sk_plan_t* plan,
 int sk_plan_check(const sk_plan_t* plan, void* stream);
 
 /* Ask for another compiled wave layout of the plan's tile (a tuning knob of the dispatcher,
- * Sec. 4.1: one kernel instance per tile configuration).  Variant 0 is the library's choice for
- * every tile; where a tile has further layouts compiled in (e.g. four waves instead of eight per
- * workgroup) they are numbered from 1; a tile without the requested variant keeps variant 0.
- * The results are the same under every variant.  Errors: INVALID_ARG (NULL plan, negative number). */
+ * Sec. 4.1: one kernel instance per tile configuration).  Variant 0 (the default) leaves the choice
+ * to the library: the tile's standard kernel, except that the 256 x 256 tiles run a four-wave
+ * kernel when the plan has no split tile and the eight-wave one when it has.  Where a tile has
+ * further layouts compiled in they are numbered from 1 (256 x 256: 1 = four waves, 2 = eight waves
+ * with the coarser MAC loop, 3 = eight waves, whatever the plan); a tile without the requested
+ * variant keeps variant 0.  The results are the same under every variant.
+ * Errors: INVALID_ARG (NULL plan, negative number). */
 int sk_plan_set_kernel_variant(sk_plan_t* plan, int variant);
 
 /* The kernel that sk_gemm would launch for this plan right now (host only, no GPU

@@ -141,12 +141,12 @@ struct Cfg {
     // PIN_ORDER: there is room to hold two operand sets, so the MAC loop pins "read the next
     // k-step's operands, then multiply the current ones".
     static constexpr int FRAG_REGS = (MI + NI) * (FP8 ? 8 : 4), ACC_REGS = MI * NI * ACC;
-    static constexpr bool PIN_ORDER = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 64 <= 256 : 2 * FRAG_REGS + 64 <= 160;
+    static constexpr bool PIN_ORDER = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 64 <= 256 : 2 * FRAG_REGS + 64 <= 192;
     // FINE: the MAC loop is written out instruction by instruction - one matrix-core instruction, then
     // at most a few LDS reads of the next k-step's operands or one LDS-DMA request, and so on - so that
     // a wave that has a SIMD to itself keeps the matrix-core pipe fed while its memory instructions
     // queue up (needs the two operand sets of PIN_ORDER).
-    static constexpr bool FINE = FINE_ != 0;
+    static constexpr bool FINE = FINE_ != 0, FINE_TAIL = FINE_ == 2;
     static_assert(!FINE || PIN_ORDER, "the instruction-by-instruction order needs two operand sets");
     // register-staged path: room to hold the next stage's pieces (4 registers each) during the matrix-core work
     static constexpr bool STAGE_AHEAD = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 4 * (CA + CB) + 64 <= 256 : 2 * FRAG_REGS + 4 * (CA + CB) + 64 <= 224;
@@ -529,13 +529,16 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         // k-step kk+1 ahead of the matrix-core work of k-step kk.  Otherwise the compiler is left
         // to order reads and matrix-core work so that one operand set suffices.
         // FINE: one k-step written out slot by slot.  Slot s = [matrix-core instruction s of the k-step
-        // on operand set `cur`] [its share of the LDS reads that fill `nxt` with the operands of k-step
-        // kk_next of stage i+1: the reads go into the first three quarters of the slots, so that the
-        // last of them has long landed when the k-step ends] [its share of request batch i, spread
-        // evenly over all slots of the trip].  A scheduling barrier after every slot keeps that order.
+        // on operand set `cur`], then either its share of the LDS reads that fill `nxt` with the operands
+        // of k-step kk_next of stage i+1 (the first three quarters of the slots) or its share of request
+        // batch i (the last quarter: a wave that has a SIMD to itself issues about five other
+        // instructions in the shadow of one matrix-core instruction, and a request is four).  A
+        // scheduling barrier after every slot keeps that order.  The reads are waited for once, at the end
+        // of the k-step (the last of them was issued a quarter of a k-step earlier), so that the next
+        // k-step carries no wait instructions.
         auto fine_step = [&](int i, int step, auto mma, auto read, const Frags<C>& cur, Frags<C>& nxt,
                              const unsigned char* a_next, const unsigned char* b_next, int kk_next, auto steady) {
-            constexpr int NM = C::MI * C::NI, R = Frags<C>::READS, NRS = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
+            constexpr int NM = C::MI * C::NI, R = Frags<C>::READS, NRS = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1, NT = NM - NRS > 0 ? NM - NRS : 1;
 #pragma unroll
             for (int s = 0; s < NM; s++) {
                 const int mi = s / C::NI, ni = s % C::NI;
@@ -545,7 +548,12 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
 #pragma unroll
                     for (int r = s * R / NRS; r < (s + 1) * R / NRS; r++) nxt.load_one(a_next, b_next, fm, kk_next, r);
                 }
-                issue_batch(i, ca, cb, step * NM + s, C::KK * NM, steady);
+                if (C::FINE_TAIL) {
+                    if (s >= NM - NT) issue_batch(i, ca, cb, step * NT + (s - (NM - NT)), C::KK * NT, steady);
+                    if (decltype(read)::value && s == NM - 1) __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only
+                } else {
+                    issue_batch(i, ca, cb, step * NM + s, C::KK * NM, steady);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -1046,6 +1054,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
 typedef void (*kernel_fn)(GemmArgs);
 struct KernelEntry {
     int dtype, bm, bn, bk, variant, fixup;
+    int whole_tiles_choice = 0;          // 1: the library launches this variant instead of variant 0 for plans without split tiles
     kernel_fn aligned, generic;
     int threads, lds_bytes, piece_elems;
     std::atomic<int> max_resident{-1};   // co-resident workgroups on the device, -1 = not yet asked
@@ -1053,16 +1062,22 @@ struct KernelEntry {
         : dtype(d), bm(m), bn(n), bk(k), variant(v), fixup(fx), aligned(a), generic(g), threads(t), lds_bytes(l), piece_elems(pe) {}
 };
 
-template <class C, bool ATOMIC = false> KernelEntry* make_entry(int variant = 0) {
-    return new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, ATOMIC ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS,
-                           streamk_gemm_kernel<C, true, ATOMIC>, streamk_gemm_kernel<C, false, ATOMIC>,
-                           C::THREADS, C::LDS_BYTES, C::PE);
+template <class C, bool ATOMIC = false> KernelEntry* make_entry(int variant = 0, int whole_tiles_choice = 0) {
+    KernelEntry* e = new KernelEntry(C::DT, C::BM, C::BN, C::BK, variant, ATOMIC ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS,
+                                     streamk_gemm_kernel<C, true, ATOMIC>, streamk_gemm_kernel<C, false, ATOMIC>,
+                                     C::THREADS, C::LDS_BYTES, C::PE);
+    e->whole_tiles_choice = whole_tiles_choice;
+    return e;
 }
 
 // Tile shapes with a kernel: <dtype, BM, BN, BK, waves along M, waves along N, matrix-core block,
 // A ring depth[, B ring depth[, instruction-by-instruction MAC loop]]>.  Variant 0 of a shape is the
 // one sk_gemm uses; other variants are alternative wave layouts of the same shape, selectable with
 // sk_plan_set_kernel_variant for tuning runs.  ATOMIC selects the atomic-add fix-up (sk_fixup).
+// The 256 x 256 tile has two kernels that the library itself chooses between: four waves (one per
+// SIMD, 128 x 128 per wave: a quarter less LDS read traffic, +1.5 - 2.5 % on problems of whole tiles)
+// for plans without split tiles, eight waves for plans with split tiles (twice as many lanes fetch
+// and add the partial tiles: 10 - 25 % faster there).
 template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int* n) {
     // The 128- and 64-row tiles run 8 waves (2 x 4), two per SIMD, like the large ones: with one wave
     // per SIMD (2 x 2) nothing overlaps a wave's waits (128 x 128 x 64: +8 - 12 % on 512 x 8192 x 8192
@@ -1078,8 +1093,9 @@ template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int
     t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>, ATOMIC>();
     if constexpr (!ATOMIC) {  // (the atomic fix-up exists for the layouts above only)
         t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>(1);
-        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2, 1>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2, 1>>(1, 1);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>(2);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2, 1>>(3);      // variant 0's kernel under a number of its own
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
         t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>(1);
         t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>(1);

@@ -77,7 +77,7 @@ def test_integer_inputs_bit_exact_every_tile_and_policy(blk, dtype):
 
 # wave layouts that are compiled in beside the default one of their tile (4 waves as 2 x 2; for the
 # 256 x 256 tile also the 8-wave kernel with the coarser MAC loop), chosen with sk_plan_set_kernel_variant
-VARIANT_TILES = [(1, (256, 128, 64)), (1, (256, 256, 64)), (1, (128, 128, 64)), (1, (64, 128, 64)), (2, (256, 256, 64))]
+VARIANT_TILES = [(1, (256, 128, 64)), (1, (256, 256, 64)), (1, (128, 128, 64)), (1, (64, 128, 64)), (2, (256, 256, 64)), (3, (256, 256, 64))]
 
 
 @pytest.mark.parametrize("variant,blk", VARIANT_TILES)
@@ -189,6 +189,10 @@ def test_fp8_integer_inputs_bit_exact(blk):
     ref = G.gemm_fp64(A, B, G.E4M3)
     for policy in range(8):
         _run_and_compare(A, B, inputs.E4M3, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True)
+    if blk[0] == 256:       # the four-wave kernel (the library's choice for plans without split tiles) under every policy
+        for policy in range(8):
+            _run_and_compare(A, B, inputs.E4M3, policy, blk, grid=24, out_dtype=sk.SK_F32, ref=ref, exact=True, variant=1)
+        _run_and_compare(A, B, inputs.E4M3, sk.SK_POLICY_ALL_SK, blk, grid=24, ref=ref, variant=1)      # bf16 output
     # unaligned K and N take the element-wise guarded path
     A, B = inputs.small_int_pair(70, 300, 203, inputs.E4M3, 32)
     ref = G.gemm_fp64(A, B, G.E4M3)

@@ -194,6 +194,18 @@ def test_kernel_info_names_the_kernel_of_a_launch():
         sk.sk_plan_set_fixup(p, sk.SK_FIXUP_ATOMIC)                # the atomic set has no variants
         assert sk.sk_plan_kernel_info(p)["variant"] == 0
         sk.sk_plan_destroy(p)
+    # a plan without split tiles on the 256 x 256 tile: the library itself takes the four-wave kernel
+    for dt, blk in ((sk.SK_BF16, (256, 256, 64)), (sk.SK_FP8_E4M3, (256, 256, 128))):
+        p = sk.sk_plan(1024, 1024, 512, sk.SK_POLICY_DP, blk, 256, dt)
+        info = sk.sk_plan_kernel_info(p)
+        assert (info["variant"], info["threads"]) == (1, 256)
+        sk.sk_plan_set_kernel_variant(p, 3)                            # the eight-wave kernel, whatever the plan
+        info = sk.sk_plan_kernel_info(p)
+        assert (info["variant"], info["threads"]) == (3, 512)
+        sk.sk_plan_destroy(p)
+        p = sk.sk_plan(1000, 1000, 1000, sk.SK_POLICY_ALL_SK, blk, 256, dt)     # split tiles: eight waves
+        assert sk.sk_plan_kernel_info(p)["threads"] == 512
+        sk.sk_plan_destroy(p)
     p = sk.sk_plan(1000, 1000, 1000, sk.SK_POLICY_DP, (64, 64, 64), 256, sk.SK_BF16)   # a tile without a kernel
     assert lib.sk_plan_kernel_info(p, None, None, None) == sk.SK_ERR_UNSUPPORTED
     sk.sk_plan_destroy(p)
