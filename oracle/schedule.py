@@ -41,7 +41,9 @@ R5  Tile index -> coordinates: row-major over the tile grid (order 0), or - beca
 R6  The workgroup whose segment holds a tile's k-iteration 0 owns the tile; the
     others store an fp32 partial in workspace slot = their workgroup id and the
     owner adds them in ascending workgroup order (= ascending k).
-R7  k_aligned=True is an execution order the paper does not have; it answers the
+    (R7 - R9 of the design notes concern the garbled statement of Algorithm 1, the
+    grid and the tile sizes; nothing in this file depends on them.)
+R10 k_aligned=True is an execution order the paper does not have; it answers the
     loss of cache locality that Sec. 5.3 remarks on.  Which workgroup runs which
     iterations is Algorithm 1's, unchanged.  A workgroup whose range contains a
     tile boundary runs its whole tiles first, then the piece at the end of its
@@ -126,26 +128,26 @@ def wg_sk_range(x, sk_iters, iters_per_wg):
 def wg_sk_segments(x, begin, end, iters_per_tile, k_aligned=False):
     """Algorithm 1, the outer loop over a workgroup's range: cut [begin, end) at tile boundaries.
 
-    k_aligned (reading R7) reorders a range that contains a tile boundary into
+    k_aligned (reading R10) reorders a range that contains a tile boundary into
     whole tiles, piece from k-iteration 0, piece up to the last k-iteration, and
     hands the OWNER role to the piece that reaches the tile's last iteration
     instead of the one that holds its first."""
     segs = []
-    it = begin
-    while it < end:
-        tile = it // iters_per_tile
-        tile_iter = tile * iters_per_tile
-        tile_iter_end = tile_iter + iters_per_tile
-        local_iter = it - tile_iter
-        local_iter_end = min(end, tile_iter_end) - tile_iter
-        if local_iter == 0 and local_iter_end == iters_per_tile:
-            role = ROLE_FULL
-        elif k_aligned:
-            role = ROLE_OWNER if local_iter_end == iters_per_tile else ROLE_CONTRIB
-        else:
-            role = ROLE_OWNER if local_iter == 0 else ROLE_CONTRIB
-        segs.append(Segment(x, tile, local_iter, local_iter_end, role))
-        it = tile_iter_end
+    if begin < end:
+        # the range touches the tiles first_tile .. last_tile; of each of them it holds the k-iterations
+        # where the range and the tile's own interval of the iteration space overlap
+        first_tile, last_tile = begin // iters_per_tile, (end - 1) // iters_per_tile
+        for tile in range(first_tile, last_tile + 1):
+            origin = tile * iters_per_tile
+            k_begin = max(begin, origin) - origin
+            k_end = min(end, origin + iters_per_tile) - origin
+            if k_begin == 0 and k_end == iters_per_tile:
+                role = ROLE_FULL
+            elif k_aligned:
+                role = ROLE_OWNER if k_end == iters_per_tile else ROLE_CONTRIB
+            else:
+                role = ROLE_OWNER if k_begin == 0 else ROLE_CONTRIB
+            segs.append(Segment(x, tile, k_begin, k_end, role))
     if k_aligned and len(segs) > 1:
         whole = [s for s in segs if s.role == ROLE_FULL]
         from_zero = [s for s in segs if s.role != ROLE_FULL and s.k_begin == 0]     # at most the last one
@@ -162,7 +164,7 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_firs
     (Sec. 3.2 / 4.1: Stream-K batches come first).  dp_first=True swaps the two
     phases - the earlier hybrid that Sec. 3.2 describes, data-parallel batches
     followed by the Stream-K work; which tiles are split and which workgroup gets
-    which work does not change.  k_aligned=True: reading R7.
+    which work does not change.  k_aligned=True: reading R10.
     """
     if min(M, N, K, blk_m, blk_n, blk_k, g) < 1:
         raise ValueError("sizes must be positive")
@@ -191,7 +193,7 @@ def plan(M, N, K, policy, blk_m, blk_n, blk_k, g, order=ORDER_ROW_MAJOR, dp_firs
 
 
 def contributors(p, owner_segment):
-    """Workgroups whose partials the owner of a split tile adds, in reduction order (R6, R7)."""
+    """Workgroups whose partials the owner of a split tile adds, in reduction order (R6, R10)."""
     ipt, ipw = p.header["iters_per_tile"], p.header["iters_per_wg"]
     assert owner_segment.role == ROLE_OWNER
     first = (owner_segment.tile * ipt) // ipw
