@@ -377,6 +377,17 @@ int bloom_query_many(const sk_bloom_t* bloom, const uint32_t* sizes, size_t n, u
  * bloom_destroy; *n_words = m_bits / 64. */
 int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** words, size_t* n_words);
 
+/* The filters as a flat byte string and back: what a tuned library ships instead of its tuning
+ * records (Sec. 4.2: the selector's table costs about one byte per profiled problem size - here
+ * n_filters * m_bits / 8 bytes whatever the number of sizes, 84 KB by default).  Little-endian:
+ * "SKBF", version 1, m_bits, k_probes, n_filters as uint32, then the 64-bit words of filter 0, 1, ...
+ * bloom_serialize: *n_bytes receives the size of the string; buf (host memory of cap bytes) receives it;
+ * (buf, cap) = (NULL, 0) asks for the size only; INVALID_ARG if cap is too small.
+ * bloom_deserialize: builds new filters from such a string (bit for bit those that were serialised);
+ * INVALID_ARG on a wrong magic, version, parameter or length. */
+int bloom_serialize(const sk_bloom_t* bloom, void* buf, size_t cap, size_t* n_bytes);
+int bloom_deserialize(const void* buf, size_t n_bytes, sk_bloom_t** out);
+
 /* Key for problem sizes that were never profiled.  The filters of Sec. 4.2 are keyed by the exact
  * (M, N, K), so a size outside the profiled set matches nothing.  This key replaces the size by
  * what decides which schedule wins under the plan's tile shape and grid: the tile shape, the

@@ -36,7 +36,7 @@ SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
            "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_plan_set_kernel_variant", "sk_gemm", "sk_gemm_static", "sk_plan_check", "sk_plan_kernel_info",
            "sk_plan_destroy", "sk_mfma_peak_operand_bytes", "sk_mfma_peak_launch", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
-           "bloom_query_many", "bloom_bits", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
+           "bloom_query_many", "bloom_bits", "bloom_serialize", "bloom_deserialize", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
 
 class sk_config(ctypes.Structure):
@@ -102,6 +102,8 @@ _lib.bloom_insert.argtypes = [_vp, ctypes.POINTER(sk_bloom_record)]
 _lib.bloom_query.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_query_many.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_bits.argtypes = [_vp, _int, ctypes.POINTER(ctypes.POINTER(ctypes.c_uint64)), ctypes.POINTER(ctypes.c_size_t)]
+_lib.bloom_serialize.argtypes = [_vp, _vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+_lib.bloom_deserialize.argtypes = [_vp, ctypes.c_size_t, ctypes.POINTER(_vp)]
 _lib.bloom_shape_key.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_murmur3_32.argtypes = [ctypes.c_char_p, ctypes.c_size_t, ctypes.c_uint32]
 _lib.bloom_murmur3_32.restype = ctypes.c_uint32
@@ -293,6 +295,23 @@ def bloom_bits(bloom, filt):
     n = ctypes.c_size_t()
     _check(_lib.bloom_bits(bloom, filt, ctypes.byref(words), ctypes.byref(n)), "bloom_bits")
     return [words[i] for i in range(n.value)]
+
+
+def bloom_serialize(bloom):
+    """The filters as bytes."""
+    n = ctypes.c_size_t()
+    _check(_lib.bloom_serialize(bloom, None, 0, ctypes.byref(n)), "bloom_serialize")
+    buf = (ctypes.c_ubyte * n.value)()
+    _check(_lib.bloom_serialize(bloom, buf, n.value, ctypes.byref(n)), "bloom_serialize")
+    return bytes(buf)
+
+
+def bloom_deserialize(data):
+    """New filters (opaque handle) from bloom_serialize's bytes."""
+    out = _vp()
+    buf = (ctypes.c_ubyte * len(data)).from_buffer_copy(data)
+    _check(_lib.bloom_deserialize(buf, len(data), ctypes.byref(out)), "bloom_deserialize")
+    return out.value
 
 
 def bloom_shape_key(plan):

@@ -137,4 +137,56 @@ extern "C" int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** 
     return SK_OK;
 }
 
+// Serialised form (little-endian): u32 magic "SKBF", u32 version, u32 m_bits, u32 k_probes,
+// u32 n_filters, then n_filters * m_bits / 64 words of 64 bits, filter by filter.
+namespace {
+constexpr uint32_t BLOOM_MAGIC = 0x46424B53u, BLOOM_VERSION = 1u;
+void put_u32(uint8_t* p, uint32_t v) { for (int i = 0; i < 4; i++) p[i] = (uint8_t)(v >> (8 * i)); }
+uint32_t get_u32(const uint8_t* p) { return (uint32_t)p[0] | (uint32_t)p[1] << 8 | (uint32_t)p[2] << 16 | (uint32_t)p[3] << 24; }
+}  // namespace
+
+extern "C" int bloom_serialize(const sk_bloom_t* bloom, void* buf, size_t cap, size_t* n_bytes) {
+    if (!bloom || !n_bytes) return SK_ERR_INVALID_ARG;
+    const size_t words = (size_t)bloom->n_filters * (bloom->m_bits / 64), need = 20 + 8 * words;
+    *n_bytes = need;
+    if (!buf || cap < need) return buf || cap ? SK_ERR_INVALID_ARG : SK_OK;     // (NULL, 0) asks for the size only
+    uint8_t* p = static_cast<uint8_t*>(buf);
+    put_u32(p, BLOOM_MAGIC); put_u32(p + 4, BLOOM_VERSION); put_u32(p + 8, bloom->m_bits);
+    put_u32(p + 12, bloom->k_probes); put_u32(p + 16, bloom->n_filters);
+    p += 20;
+    for (const std::vector<uint64_t>& f : bloom->filters)
+        for (uint64_t w : f) {
+            put_u32(p, (uint32_t)w); put_u32(p + 4, (uint32_t)(w >> 32));
+            p += 8;
+        }
+    return SK_OK;
+}
+
+extern "C" int bloom_deserialize(const void* buf, size_t n_bytes, sk_bloom_t** out) {
+    if (!buf || !out || n_bytes < 20) return SK_ERR_INVALID_ARG;
+    const uint8_t* p = static_cast<const uint8_t*>(buf);
+    if (get_u32(p) != BLOOM_MAGIC || get_u32(p + 4) != BLOOM_VERSION) return SK_ERR_INVALID_ARG;
+    const uint32_t m_bits = get_u32(p + 8), k_probes = get_u32(p + 12), n_filters = get_u32(p + 16);
+    if (!m_bits || m_bits % 64 || !k_probes || k_probes > 64 || !n_filters || n_filters > 32) return SK_ERR_INVALID_ARG;
+    const size_t words = (size_t)n_filters * (m_bits / 64);
+    if (n_bytes != 20 + 8 * words) return SK_ERR_INVALID_ARG;
+    sk_bloom_t* b = new (std::nothrow) sk_bloom_t;
+    if (!b) return SK_ERR_NOMEM;
+    b->m_bits = m_bits; b->k_probes = k_probes; b->n_filters = n_filters;
+    try {
+        b->filters.assign(n_filters, std::vector<uint64_t>(m_bits / 64, 0));
+    } catch (const std::bad_alloc&) {
+        delete b;
+        return SK_ERR_NOMEM;
+    }
+    p += 20;
+    for (std::vector<uint64_t>& f : b->filters)
+        for (uint64_t& w : f) {
+            w = (uint64_t)get_u32(p) | (uint64_t)get_u32(p + 4) << 32;
+            p += 8;
+        }
+    *out = b;
+    return SK_OK;
+}
+
 extern "C" void bloom_destroy(sk_bloom_t* bloom) { delete bloom; }

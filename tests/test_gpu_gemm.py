@@ -130,6 +130,41 @@ def test_bit_identical_run_to_run_and_flag_reuse():
     r2.close()
 
 
+def test_flag_exchange_soak_two_plans_one_workspace():
+    """2000 launches on one stream alternating a plan whose tiles are reduced flat (15 contributors) and
+    one reduced in two levels (about 60 per tile), both on the same workspace memory: every result must
+    be bit-identical to the plan's first one and no owner may time out.  Stops at the first failure."""
+    c = inputs.config1()
+    A2, B2 = inputs.uniform_pair(64, 208, 7872, inputs.BF16, 77)
+    dA1, dB1, dA2, dB2 = to_device(c["A"]), to_device(c["B"]), to_device(A2), to_device(B2)
+    r1 = Runner(512, 512, 512, sk.SK_POLICY_ALL_SK, c["blk"], 256, inputs.F16, sk.SK_F32)
+    r2 = Runner(64, 208, 7872, sk.SK_POLICY_ALL_SK, (32, 128, 64), 256, inputs.BF16, sk.SK_F32)
+    try:
+        # one workspace for both plans (the larger need), as a serving loop would hold it
+        need = max(sk.sk_workspace_bytes(r1.plan), sk.sk_workspace_bytes(r2.plan))
+        ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+        base = (ws.data_ptr() + 255) // 256 * 256
+        sk.sk_plan_set_workspace(r1.plan, base, need)
+        sk.sk_plan_set_workspace(r2.plan, base, need)
+        first1, first2 = r1.run(dA1, dB1).clone(), r2.run(dA2, dB2).clone()
+        assert r1.check() == sk.SK_OK and r2.check() == sk.SK_OK
+        assert G.rel_error(r1.result(first1), G.gemm_fp64(c["A"], c["B"], G.F16)) <= TOL_32
+        assert G.rel_error(r2.result(first2), G.gemm_fp64(A2, B2, G.BF16)) <= TOL_32
+        for i in range(1000):
+            d1 = r1.run(dA1, dB1)
+            d2 = r2.run(dA2, dB2)
+            if i % 8 == 7 or i == 999:            # compare (and with it synchronise) every eighth pair; the launches in between queue up back to back
+                assert torch.equal(d1, first1), "flat plan differs at launch pair %d" % i
+                assert torch.equal(d2, first2), "two-level plan differs at launch pair %d" % i
+                assert r1.check() == sk.SK_OK and r2.check() == sk.SK_OK, "time-out at launch pair %d" % i
+            else:
+                d1.fill_(0)                        # so that a launch that stores nothing cannot pass
+                d2.fill_(0)
+    finally:
+        r1.close()
+        r2.close()
+
+
 def test_owner_timeout_is_reported_and_every_wave_exits():
     c = inputs.config1()
     dA, dB = to_device(c["A"]), to_device(c["B"])

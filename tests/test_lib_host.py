@@ -243,6 +243,39 @@ def test_bloom_bits_and_queries_bit_exact_with_oracle(params):
     sk.bloom_destroy(b)
 
 
+@pytest.mark.parametrize("params", [(0, 0, 0), (640, 3, 5)])
+def test_bloom_serialised_filters_round_trip_bit_exact(params):
+    # the byte string holds exactly the oracle's words (little-endian, filter by filter) behind a 20-byte
+    # header, and filters rebuilt from it answer like the oracle
+    recs = _records(300, 11)
+    b = sk.bloom_build(recs, *params)
+    o = Bm.build(recs, *(p or d for p, d in zip(params, (Bm.M_BITS, Bm.K_PROBES, Bm.N_FILTERS))))
+    data = sk.bloom_serialize(b)
+    assert len(data) == 20 + o.n_filters * o.m_bits // 8
+    assert data[:4] == b"SKBF" and int.from_bytes(data[4:8], "little") == 1
+    assert [int.from_bytes(data[8 + 4 * i:12 + 4 * i], "little") for i in range(3)] == [o.m_bits, o.k_probes, o.n_filters]
+    body = b"".join(w.to_bytes(8, "little") for f in range(o.n_filters) for w in o.words[f])
+    assert data[20:] == body
+    c = sk.bloom_deserialize(data)
+    for f in range(o.n_filters):
+        assert sk.bloom_bits(c, f) == o.words[f]
+    rng = random.Random(12)
+    for M, N, K in [r[:3] for r in recs[:100]] + [(rng.randint(1, 70000), rng.randint(1, 70000), rng.randint(1, 70000)) for _ in range(300)]:
+        assert sk.bloom_query(c, M, N, K) == o.query(M, N, K)
+    lib = sk.binding._lib
+    out, n = ctypes.c_void_p(), ctypes.c_size_t()
+    bad = [data[:-1], data + b"x", b"XKBF" + data[4:], data[:4] + (2).to_bytes(4, "little") + data[8:],
+           data[:8] + (65).to_bytes(4, "little") + data[12:], data[:19]]
+    for d in bad:
+        buf = (ctypes.c_ubyte * len(d)).from_buffer_copy(d)
+        assert lib.bloom_deserialize(buf, len(d), ctypes.byref(out)) == sk.SK_ERR_INVALID_ARG and not out.value
+    small = (ctypes.c_ubyte * 16)()
+    assert lib.bloom_serialize(b, small, 16, ctypes.byref(n)) == sk.SK_ERR_INVALID_ARG and n.value == len(data)
+    assert lib.bloom_serialize(None, None, 0, ctypes.byref(n)) == sk.SK_ERR_INVALID_ARG
+    sk.bloom_destroy(b)
+    sk.bloom_destroy(c)
+
+
 @settings(max_examples=200, deadline=None)
 @given(st.tuples(st.integers(1, 20000), st.integers(1, 20000), st.integers(1, 70000)),
        st.sampled_from([(256, 256, 64), (128, 128, 64), (32, 128, 64), (16, 128, 32)]),
