@@ -1074,10 +1074,11 @@ template <class C, bool ATOMIC = false> KernelEntry* make_entry(int variant = 0,
 // A ring depth[, B ring depth[, instruction-by-instruction MAC loop]]>.  Variant 0 of a shape is the
 // one sk_gemm uses; other variants are alternative wave layouts of the same shape, selectable with
 // sk_plan_set_kernel_variant for tuning runs.  ATOMIC selects the atomic-add fix-up (sk_fixup).
-// The 256 x 256 tile has two kernels that the library itself chooses between: four waves (one per
-// SIMD, 128 x 128 per wave: a quarter less LDS read traffic, +1.5 - 2.5 % on problems of whole tiles)
-// for plans without split tiles, eight waves for plans with split tiles (twice as many lanes fetch
-// and add the partial tiles: 10 - 25 % faster there).
+// The three compute-bound shapes have two kernels that the library itself chooses between: four
+// waves (one per SIMD, twice the tile per wave: a quarter less LDS read traffic, +1.5 - 3 % on problems
+// of whole tiles) for plans without split tiles, eight waves for plans with split tiles (twice as
+// many lanes fetch and add the partial tiles: 10 - 25 % faster there with 256 x 256 tiles).  Variant 3
+// is the eight-wave kernel under a number of its own (variant 0 means "the library's choice").
 template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int* n) {
     // The 128- and 64-row tiles run 8 waves (2 x 4), two per SIMD, like the large ones: with one wave
     // per SIMD (2 x 2) nothing overlaps a wave's waits (128 x 128 x 64: +8 - 12 % on 512 x 8192 x 8192
@@ -1092,12 +1093,14 @@ template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int
     t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>, ATOMIC>();
     if constexpr (!ATOMIC) {  // (the atomic fix-up exists for the layouts above only)
-        t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3, 3, 1>>(1, 1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3, 3, 1>>(3);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2, 1>>(1, 1);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>(2);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2, 1>>(3);      // variant 0's kernel under a number of its own
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();
-        t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3>>(1);
+        t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 2, 32, 3, 3, 1>>(1, 1);
+        t[(*n)++] = make_entry<Cfg<DT, 128, 128, 64, 2, 4, 32, 3, 3, 1>>(3);
         t[(*n)++] = make_entry<Cfg<DT, 64, 128, 64, 2, 2, 32, 4>>(1);
     }
 }

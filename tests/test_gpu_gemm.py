@@ -77,7 +77,8 @@ def test_integer_inputs_bit_exact_every_tile_and_policy(blk, dtype):
 
 # wave layouts that are compiled in beside the default one of their tile (4 waves as 2 x 2; for the
 # 256 x 256 tile also the 8-wave kernel with the coarser MAC loop), chosen with sk_plan_set_kernel_variant
-VARIANT_TILES = [(1, (256, 128, 64)), (1, (256, 256, 64)), (1, (128, 128, 64)), (1, (64, 128, 64)), (2, (256, 256, 64)), (3, (256, 256, 64))]
+VARIANT_TILES = [(1, (256, 128, 64)), (1, (256, 256, 64)), (1, (128, 128, 64)), (1, (64, 128, 64)), (2, (256, 256, 64)), (3, (256, 256, 64)),
+                 (3, (256, 128, 64)), (3, (128, 128, 64))]
 
 
 @pytest.mark.parametrize("variant,blk", VARIANT_TILES)
