@@ -25,8 +25,8 @@ GRID, BK = 256, 64
 # The constants as they stand in csrc/streamk_plan.cpp (tile_costs, model_tile_us, model_exchange_us).
 # The library's C++ code is what runs; predict() below restates its formula for the fit, and
 # tests/test_selector.py checks that predict() with these constants picks sk_default_tile's tile.
-LIBRARY = {"tflops": {(256, 256): 976., (256, 128): 928., (128, 128): 848., (64, 128): 671., (32, 128): 464., (16, 128): 78.},
-           "tile_us": 0.63, "tile_bytes_per_us": 54.8e3, "part_us": 2.64, "part_bytes_per_us": 59.9e3}
+LIBRARY = {"tflops": {(256, 256): 1170., (256, 128): 1027., (128, 128): 826., (64, 128): 624., (32, 128): 297., (16, 128): 47.},
+           "tile_us": 0.69, "tile_bytes_per_us": 8.86e3, "part_us": 5.77, "part_bytes_per_us": 35.9e3}
 
 
 def cdiv(a, b):

@@ -334,7 +334,7 @@ def test_plan_estimate_properties():
     # Stream-K batch over the 257 tiles (SK2_DP here) costs one iteration more per workgroup plus an exchange
     dp = est(4096 + 256, 4096, 4096, sk.SK_POLICY_DP, (256, 256, 64))   # 17 x 16 = 272 tiles
     sk2 = est(4096 + 256, 4096, 4096, sk.SK_POLICY_SK2_DP, (256, 256, 64))
-    assert dp > 1.9 * one and one < sk2 < 1.3 * one
+    assert dp > 1.9 * one and one < sk2 < 0.75 * dp
     # 210 tiles of 256 x 256 over a short K: splitting saves a sixth of the iterations, but 250 workgroups
     # then park and fetch a 256 KB partial tile each - measured 99 us against 64 us data-parallel
     assert est(2560, 5280, 2160, sk.SK_POLICY_DP, blk) < est(2560, 5280, 2160, sk.SK_POLICY_ALL_SK, blk)
