@@ -12,7 +12,8 @@ of each counter is worth in bytes:
     python3 -m paper_2408_11417_amd.hbm_traffic --runs out --library-commit $(git rev-parse --short HEAD) \\
         --entry cfg5:DP --out profiles/hbm_traffic_streamk_gemm_kernel.txt
 
-Each --entry NAME:POLICY reads out/fetch_NAME and out/write_NAME.  The counters are in KiB per dispatch.
+Each --entry NAME:POLICY[,POLICY...] reads out/fetch_NAME and out/write_NAME (several policy names for one
+run: policies that are the same schedule on that workload, e.g. all seven on whole waves of tiles).  The counters are in KiB per dispatch.
 The calibration factor is (bytes the copy moves) / (bytes the counter reports for the copy kernel).
 CPU only; reads CSV files, nothing else.
 """
@@ -52,7 +53,7 @@ def counter_per_dispatch(run_dir, counter, kernel_substr, biggest=False):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--runs", required=True, help="folder holding fetch_NAME / write_NAME / fetch_copy / write_copy run folders")
-    ap.add_argument("--entry", action="append", default=[], help="NAME:POLICY, e.g. cfg5:DP (repeatable)")
+    ap.add_argument("--entry", action="append", default=[], help="NAME:POLICY[,POLICY...], e.g. cfg5:DP (repeatable)")
     ap.add_argument("--library-commit", default="unknown")
     ap.add_argument("--out", required=True)
     args = ap.parse_args()
@@ -68,7 +69,8 @@ def main():
         name, _, policy = e.partition(":")
         f = counter_per_dispatch(os.path.join(args.runs, "fetch_" + name), "FETCH_SIZE", "streamk_gemm_kernel") * kib * f_scale
         w = counter_per_dispatch(os.path.join(args.runs, "write_" + name), "WRITE_SIZE", "streamk_gemm_kernel") * kib * w_scale
-        lines.append("%s %s %.4g %.4g" % (name, policy, f, w))
+        for pol in policy.split(","):
+            lines.append("%s %s %.4g %.4g" % (name, pol, f, w))
     with open(args.out, "w") as fh:
         fh.write("\n".join(lines) + "\n")
     print("\n".join(lines))
