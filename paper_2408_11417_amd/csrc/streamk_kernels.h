@@ -146,7 +146,7 @@ struct Cfg {
     // at most a few LDS reads of the next k-step's operands or one LDS-DMA request, and so on - so that
     // a wave that has a SIMD to itself keeps the matrix-core pipe fed while its memory instructions
     // queue up (needs the two operand sets of PIN_ORDER).
-    static constexpr bool FINE = FINE_ != 0, FINE_TAIL = FINE_ == 2;
+    static constexpr bool FINE = FINE_ != 0;
     static_assert(!FINE || PIN_ORDER, "the instruction-by-instruction order needs two operand sets");
     // register-staged path: room to hold the next stage's pieces (4 registers each) during the matrix-core work
     static constexpr bool STAGE_AHEAD = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 4 * (CA + CB) + 64 <= 256 : 2 * FRAG_REGS + 4 * (CA + CB) + 64 <= 224;
@@ -529,16 +529,15 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         // k-step kk+1 ahead of the matrix-core work of k-step kk.  Otherwise the compiler is left
         // to order reads and matrix-core work so that one operand set suffices.
         // FINE: one k-step written out slot by slot.  Slot s = [matrix-core instruction s of the k-step
-        // on operand set `cur`], then either its share of the LDS reads that fill `nxt` with the operands
-        // of k-step kk_next of stage i+1 (the first three quarters of the slots) or its share of request
-        // batch i (the last quarter: a wave that has a SIMD to itself issues about five other
-        // instructions in the shadow of one matrix-core instruction, and a request is four).  A
-        // scheduling barrier after every slot keeps that order.  The reads are waited for once, at the end
-        // of the k-step (the last of them was issued a quarter of a k-step earlier), so that the next
-        // k-step carries no wait instructions.
+        // on operand set `cur`] [its share of the LDS reads that fill `nxt` with the operands of k-step
+        // kk_next of stage i+1: the reads go into the first three quarters of the slots, so that the
+        // last of them has long landed when the k-step ends] [its share of request batch i, spread
+        // evenly over all slots of the trip].  A scheduling barrier after every slot keeps that order:
+        // a wave that has a SIMD to itself issues about five other instructions in the shadow of one
+        // matrix-core instruction, and issued in a block they would drain the matrix-core pipe.
         auto fine_step = [&](int i, int step, auto mma, auto read, const Frags<C>& cur, Frags<C>& nxt,
                              const unsigned char* a_next, const unsigned char* b_next, int kk_next, auto steady) {
-            constexpr int NM = C::MI * C::NI, R = Frags<C>::READS, NRS = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1, NT = NM - NRS > 0 ? NM - NRS : 1;
+            constexpr int NM = C::MI * C::NI, R = Frags<C>::READS, NRS = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
 #pragma unroll
             for (int s = 0; s < NM; s++) {
                 const int mi = s / C::NI, ni = s % C::NI;
@@ -548,12 +547,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
 #pragma unroll
                     for (int r = s * R / NRS; r < (s + 1) * R / NRS; r++) nxt.load_one(a_next, b_next, fm, kk_next, r);
                 }
-                if (C::FINE_TAIL) {
-                    if (s >= NM - NT) issue_batch(i, ca, cb, step * NT + (s - (NM - NT)), C::KK * NT, steady);
-                    if (decltype(read)::value && s == NM - 1) __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0) only
-                } else {
-                    issue_batch(i, ca, cb, step * NM + s, C::KK * NM, steady);
-                }
+                issue_batch(i, ca, cb, step * NM + s, C::KK * NM, steady);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
