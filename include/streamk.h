@@ -295,7 +295,8 @@ int sk_plan_check(const sk_plan_t* plan, void* stream);
 /* Ask for another compiled wave layout of the plan's tile (a tuning knob of the dispatcher,
  * Sec. 4.1: one kernel instance per tile configuration).  Variant 0 (the default) leaves the choice
  * to the library: the tile's standard kernel, except that the 256 x 256, 256 x 128 and 128 x 128 x 64
- * tiles run a four-wave kernel when the plan has no split tile and the eight-wave one when it has.
+ * tiles run a four-wave kernel when the plan has no split tile (and, for the 256-row tiles, enough
+ * K-iterations per tile: 48 and 16) and the eight-wave one otherwise.
  * Where a tile has further layouts compiled in they are numbered from 1 (for those three tiles: 1 = four
  * waves, 3 = eight waves, whatever the plan; 256 x 256 also 2 = eight waves with the coarser MAC loop);
  * a tile without the requested variant keeps variant 0.  The results are the same under every variant.

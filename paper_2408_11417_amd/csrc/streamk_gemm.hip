@@ -24,15 +24,16 @@ KernelEntry** kernel_table(int* count) {
 
 // The kernel for a tile shape, input type and fix-up mode: the wanted variant if the shape has it,
 // else the shape's variant 0.  want = 0 leaves the choice to the library: variant 0, except that a plan
-// without split tiles gets the variant marked for such plans where the shape has one.
-KernelEntry* find_kernel(int dtype, int bm, int bn, int bk, int fixup = SK_FIXUP_FLAGS, int want = 0, bool whole_tiles = false) {
+// without split tiles (whole_tile_iters = its k-iterations per tile, 0 for plans with split tiles) gets
+// the variant marked for such plans where the shape has one and the tiles are deep enough.
+KernelEntry* find_kernel(int dtype, int bm, int bn, int bk, int fixup = SK_FIXUP_FLAGS, int want = 0, int whole_tile_iters = 0) {
     int n;
     KernelEntry** t = kernel_table(&n);
     KernelEntry* fallback = nullptr;
     KernelEntry* exact = nullptr;
     for (int i = 0; i < n; i++)
         if (t[i]->dtype == dtype && t[i]->bm == bm && t[i]->bn == bn && t[i]->bk == bk && t[i]->fixup == fixup) {
-            if (want == 0 && whole_tiles && t[i]->whole_tiles_choice) return t[i];
+            if (want == 0 && t[i]->whole_tiles_choice && whole_tile_iters >= t[i]->whole_tiles_choice) return t[i];
             if (t[i]->variant == want) exact = t[i];
             if (t[i]->variant == 0) fallback = t[i];
         }
@@ -97,7 +98,7 @@ extern "C" int sk_plan_kernel_info(const sk_plan_t* plan, int32_t* threads, int3
     if (!plan) return SK_ERR_INVALID_ARG;
     const sk_plan_header& h = plan->h;
     const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
-    const KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant, !plan->needs_fixup);
+    const KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant, plan->needs_fixup ? 0 : plan->h.iters_per_tile);
     if (!e) return SK_ERR_UNSUPPORTED;
     if (threads) *threads = e->threads;
     if (lds_bytes) *lds_bytes = e->lds_bytes;
@@ -119,7 +120,7 @@ int launch_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, vo
         return SK_ERR_UNSUPPORTED;
     // plans without split tiles run the plain kernel under either fix-up mode
     const bool atomic = plan->fixup == SK_FIXUP_ATOMIC && plan->needs_fixup;
-    KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant, !plan->needs_fixup);
+    KernelEntry* e = find_kernel(h.in_dtype, h.blk_m, h.blk_n, h.blk_k, atomic ? SK_FIXUP_ATOMIC : SK_FIXUP_FLAGS, plan->kernel_variant, plan->needs_fixup ? 0 : plan->h.iters_per_tile);
     if (!e) return SK_ERR_UNSUPPORTED;
     if (plan->needs_fixup && !workspace && !(atomic && h.out_dtype == SK_F32)) return SK_ERR_WORKSPACE;
     const bool aligned = (h.K % e->piece_elems == 0) && (h.N % e->piece_elems == 0);   // whole 16-byte pieces per row

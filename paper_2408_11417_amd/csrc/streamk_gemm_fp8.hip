@@ -4,7 +4,7 @@
 namespace streamk_detail {
 void register_fp8(KernelEntry** t, int* n) {
     t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 4, 32, 3, 2>>();
-    t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 2, 32, 3, 2, 1>>(1, 1);   // four waves: plans without split tiles (+2 - 3 %)
+    t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 2, 32, 3, 2, 1>>(1, 48);   // four waves: plans without split tiles and K >= 6144 (+2 - 3 %)
     t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 128, 256, 128, 2, 4, 32, 3, 3>>();
     t[(*n)++] = make_entry<Cfg<SK_FP8_E4M3, 256, 256, 128, 2, 4, 32, 3, 2>>(3);             // variant 0's kernel under a number of its own
 }

@@ -1048,7 +1048,8 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
 typedef void (*kernel_fn)(GemmArgs);
 struct KernelEntry {
     int dtype, bm, bn, bk, variant, fixup;
-    int whole_tiles_choice = 0;          // 1: the library launches this variant instead of variant 0 for plans without split tiles
+    int whole_tiles_choice = 0;          // > 0: the library launches this variant instead of variant 0 for plans without split
+                                         // tiles whose tiles have at least this many k-iterations
     kernel_fn aligned, generic;
     int threads, lds_bytes, piece_elems;
     std::atomic<int> max_resident{-1};   // co-resident workgroups on the device, -1 = not yet asked
@@ -1087,9 +1088,9 @@ template <int DT, bool ATOMIC = false> void add_16bit_tiles(KernelEntry** t, int
     t[(*n)++] = make_entry<Cfg<DT, 32, 128, 64, 1, 4, 32, 4>, ATOMIC>();
     t[(*n)++] = make_entry<Cfg<DT, 16, 128, 64, 1, 4, 16, 4>, ATOMIC>();
     if constexpr (!ATOMIC) {  // (the atomic fix-up exists for the layouts above only)
-        t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3, 3, 1>>(1, 1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 2, 2, 32, 3, 3, 1>>(1, 16);
         t[(*n)++] = make_entry<Cfg<DT, 256, 128, 64, 4, 2, 32, 3, 3, 1>>(3);
-        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2, 1>>(1, 1);
+        t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 2, 32, 3, 2, 1>>(1, 48);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2>>(2);
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 64, 2, 4, 32, 3, 2, 1>>(3);      // variant 0's kernel under a number of its own
         t[(*n)++] = make_entry<Cfg<DT, 256, 256, 32, 2, 2, 32, 4>>();

@@ -196,7 +196,10 @@ def test_kernel_info_names_the_kernel_of_a_launch():
         sk.sk_plan_destroy(p)
     # a plan without split tiles on the 256 x 256 tile: the library itself takes the four-wave kernel
     for dt, blk in ((sk.SK_BF16, (256, 256, 64)), (sk.SK_FP8_E4M3, (256, 256, 128))):
-        p = sk.sk_plan(1024, 1024, 512, sk.SK_POLICY_DP, blk, 256, dt)
+        p = sk.sk_plan(1024, 1024, 512, sk.SK_POLICY_DP, blk, 256, dt)       # 8 (4) k-iterations per tile: too shallow for it
+        assert sk.sk_plan_kernel_info(p)["threads"] == 512
+        sk.sk_plan_destroy(p)
+        p = sk.sk_plan(1024, 1024, 6144, sk.SK_POLICY_DP, blk, 256, dt)
         info = sk.sk_plan_kernel_info(p)
         assert (info["variant"], info["threads"]) == (1, 256)
         sk.sk_plan_set_kernel_variant(p, 3)                            # the eight-wave kernel, whatever the plan
