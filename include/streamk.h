@@ -361,6 +361,12 @@ typedef struct {
 
 typedef struct sk_bloom_t sk_bloom_t;
 
+/* The winner mask of one profiled problem size (Sec. 4.2: the winning configurations are inserted;
+ * Sec. 5.2's tolerance thresholds widen "winning"): bit p of *mask_out is set iff policy p's time is
+ * within tolerance of the fastest, times_ns[p] * 1000 <= min(times_ns) * (1000 + tol_permille), in
+ * integers.  times_ns: host int64[n], 1 <= n <= 32, each in [0, 2^40].  Errors: INVALID_ARG. */
+int bloom_winner_mask(const int64_t* times_ns, size_t n, uint32_t tol_permille, uint32_t* mask_out);
+
 /* Build the filters from n records (host memory; n may be 0).  params may be NULL. */
 int bloom_build(const sk_bloom_record* recs, size_t n, const sk_bloom_params* params, sk_bloom_t** out);
 

@@ -35,7 +35,7 @@ SK_SEGMENTS_ASCENDING, SK_SEGMENTS_K_ALIGNED = 0, 1
 
 EXPORTS = ("sk_plan", "sk_plan_info", "sk_plan_ranges", "sk_plan_segments", "sk_plan_tile_coords", "sk_workspace_bytes",
            "sk_plan_set_fixup", "sk_plan_set_batch_order", "sk_plan_set_segment_order", "sk_plan_set_workspace", "sk_plan_set_spin_limit", "sk_plan_set_kernel_variant", "sk_gemm", "sk_gemm_static", "sk_plan_check", "sk_plan_kernel_info",
-           "sk_plan_destroy", "sk_mfma_peak_operand_bytes", "sk_mfma_peak_launch", "sk_default_tile", "sk_plan_estimate_us", "bloom_build", "bloom_insert", "bloom_query",
+           "sk_plan_destroy", "sk_mfma_peak_operand_bytes", "sk_mfma_peak_launch", "sk_default_tile", "sk_plan_estimate_us", "bloom_winner_mask", "bloom_build", "bloom_insert", "bloom_query",
            "bloom_query_many", "bloom_bits", "bloom_serialize", "bloom_deserialize", "bloom_shape_key", "bloom_murmur3_32", "bloom_destroy", "sk_status_str", "sk_last_hip_error")
 
 
@@ -102,6 +102,7 @@ _lib.bloom_insert.argtypes = [_vp, ctypes.POINTER(sk_bloom_record)]
 _lib.bloom_query.argtypes = [_vp, _i64, _i64, _i64, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_query_many.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_bits.argtypes = [_vp, _int, ctypes.POINTER(ctypes.POINTER(ctypes.c_uint64)), ctypes.POINTER(ctypes.c_size_t)]
+_lib.bloom_winner_mask.argtypes = [ctypes.POINTER(ctypes.c_int64), ctypes.c_size_t, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32)]
 _lib.bloom_serialize.argtypes = [_vp, _vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
 _lib.bloom_deserialize.argtypes = [_vp, ctypes.c_size_t, ctypes.POINTER(_vp)]
 _lib.bloom_shape_key.argtypes = [_vp, ctypes.POINTER(ctypes.c_uint32)]
@@ -258,6 +259,14 @@ def sk_plan_kernel_info(plan):
 
 def sk_plan_destroy(plan):
     _lib.sk_plan_destroy(plan)
+
+
+def bloom_winner_mask(times_ns, tol_permille):
+    """Bit p set iff times_ns[p] is within tol_permille / 1000 of the fastest."""
+    arr = (ctypes.c_int64 * len(times_ns))(*[int(t) for t in times_ns])
+    mask = ctypes.c_uint32()
+    _check(_lib.bloom_winner_mask(arr, len(times_ns), tol_permille, ctypes.byref(mask)), "bloom_winner_mask")
+    return mask.value
 
 
 def bloom_build(records, m_bits=0, k_probes=0, n_filters=0):

@@ -137,6 +137,20 @@ extern "C" int bloom_bits(const sk_bloom_t* bloom, int filter, const uint64_t** 
     return SK_OK;
 }
 
+extern "C" int bloom_winner_mask(const int64_t* times_ns, size_t n, uint32_t tol_permille, uint32_t* mask_out) {
+    if (!times_ns || !mask_out || n < 1 || n > 32 || tol_permille > 1000000u) return SK_ERR_INVALID_ARG;
+    int64_t best = times_ns[0];
+    for (size_t p = 0; p < n; p++) {
+        if (times_ns[p] < 0 || times_ns[p] > (int64_t)1 << 40) return SK_ERR_INVALID_ARG;     // (keeps the products below in 64 bits)
+        if (times_ns[p] < best) best = times_ns[p];
+    }
+    uint32_t mask = 0;
+    for (size_t p = 0; p < n; p++)
+        if (times_ns[p] * 1000 <= best * (1000 + (int64_t)tol_permille)) mask |= 1u << p;
+    *mask_out = mask;
+    return SK_OK;
+}
+
 // Serialised form (little-endian): u32 magic "SKBF", u32 version, u32 m_bits, u32 k_probes,
 // u32 n_filters, then n_filters * m_bits / 64 words of 64 bits, filter by filter.
 namespace {

@@ -24,10 +24,8 @@ N_POL = sk.SK_NUM_POLICIES
 
 
 def winner_mask(times_ns, tol):
-    """Bit p set iff policy p is within (1 + tol) of the fastest (integer arithmetic in permille)."""
-    best = min(times_ns)
-    permille = int(round(tol * 1000))
-    return sum(1 << p for p, t in enumerate(times_ns) if t * 1000 <= best * (1000 + permille))
+    """Bit p set iff policy p is within (1 + tol) of the fastest (the library's integer rule, bloom_winner_mask)."""
+    return sk.bloom_winner_mask(times_ns, int(round(tol * 1000)))
 
 
 def shape_key(M, N, K, tile=None, grid=256, in_dtype=sk.SK_BF16):

@@ -147,3 +147,17 @@ def test_fit_tool_formula_is_the_library_cost_model():
         finally:
             sk.sk_plan_destroy(plan)
     assert tuple(sk.sk_default_tile(8192, 8192, 8192, sk.SK_FP8_E4M3)) == (256, 256, 128)
+
+
+def test_winner_mask_error_paths_and_hand_values():
+    import ctypes
+    lib = sk.binding._lib
+    out = ctypes.c_uint32(77)
+    arr = (ctypes.c_int64 * 3)(100, 120, 121)
+    assert lib.bloom_winner_mask(arr, 3, 200, ctypes.byref(out)) == sk.SK_OK and out.value == 0b011      # 120 <= 100 * 1.2 < 121
+    assert lib.bloom_winner_mask(arr, 3, 0, ctypes.byref(out)) == sk.SK_OK and out.value == 0b001
+    out.value = 77
+    assert lib.bloom_winner_mask(arr, 0, 0, ctypes.byref(out)) == sk.SK_ERR_INVALID_ARG and out.value == 77
+    assert lib.bloom_winner_mask(None, 3, 0, ctypes.byref(out)) == sk.SK_ERR_INVALID_ARG
+    neg = (ctypes.c_int64 * 2)(-1, 5)
+    assert lib.bloom_winner_mask(neg, 2, 0, ctypes.byref(out)) == sk.SK_ERR_INVALID_ARG and out.value == 77
