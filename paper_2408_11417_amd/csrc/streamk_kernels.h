@@ -150,6 +150,9 @@ struct Cfg {
     static_assert(!FINE || PIN_ORDER, "the instruction-by-instruction order needs two operand sets");
     // register-staged path: room to hold the next stage's pieces (4 registers each) during the matrix-core work
     static constexpr bool STAGE_AHEAD = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 4 * (CA + CB) + 64 <= 256 : 2 * FRAG_REGS + 4 * (CA + CB) + 64 <= 224;
+    // vector stores one wave issues in the epilogue of an unsplit interior tile with 16-bit output (an fp32
+    // output issues more): what may still be in flight when the next tile's first stage is waited for
+    static constexpr int EPILOGUE_STORES = MI * NI * (MF == 32 ? ACC / 8 : ACC / 4);
     static_assert(WTM % MF == 0 && WTN % MF == 0 && BK % KM == 0, "tile does not divide");
     static_assert(CPA == 4 || CPA == 8 || CPA == 16, "A swizzle assumes 64/128/256-byte rows");
     static_assert(CPB >= 16, "B swizzle assumes rows of at least 256 bytes");
@@ -443,10 +446,12 @@ __device__ __forceinline__ u16 to_bf16_bits(float f) {
     return __builtin_bit_cast(u16, (__bf16)f);     // round to nearest even (one hardware instruction on gfx950)
 }
 
-template <class C, int LATER> __device__ __forceinline__ void wait_stage(int later) {
-    // wait until the loads of the wanted stage have landed, given how many stages follow it
-    if (LATER == 0 || later >= LATER) wait_vmcnt<C::in_flight(LATER)>();
-    else wait_stage<C, (LATER > 0 ? LATER - 1 : 0)>(later);
+template <class C, int LATER, int EXTRA = 0> __device__ __forceinline__ void wait_stage(int later) {
+    // wait until the loads of the wanted stage have landed, given how many stages follow it; EXTRA:
+    // vector-memory instructions that this wave is known to have issued after those loads besides the
+    // later stages' loads (the counter retires in issue order, so they may stay in flight)
+    if (LATER == 0 || later >= LATER) wait_vmcnt<(C::in_flight(LATER) + EXTRA < 63 ? C::in_flight(LATER) + EXTRA : 63)>();
+    else wait_stage<C, (LATER > 0 ? LATER - 1 : 0), EXTRA>(later);
 }
 
 // The matrix-core work of one k-step.
@@ -474,6 +479,42 @@ __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const un
     }
 }
 
+// Slice `step` of `steps` of request batch j of a segment (k-iterations k_begin .. k_begin + nk - 1 of a
+// tile): the B tile of stage j + NSB, then the A tile of stage j + NSA, into ring slots slot_b / slot_a.
+// STEADY: the caller knows that both stages exist and lie entirely inside K.
+template <class C, bool STEADY>
+__device__ __forceinline__ void issue_requests(const GemmArgs& g, const DmaMap<C>& dm, uint32_t lds0, int k_begin, int nk, int full_k,
+                                               int j, int slot_a, int slot_b, int step, int steps) {
+    const int ib = j + C::NSB, ia = j + C::NSA;
+    const int q0 = step * C::LPS / steps, q1 = (step + 1) * C::LPS / steps;
+    const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
+    const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
+    if ((STEADY || (ib >= 0 && ib < nk)) && b1 > b0) {
+        const uint32_t lds = lds0 + C::B_RING + slot_b * C::B_BYTES;
+        if (STEADY || k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
+        else dm.template issue_b<true>(g, k_begin + ib, lds, b0, b1);
+    }
+    if ((STEADY || (ia >= 0 && ia < nk)) && a1 > a0) {
+        const uint32_t lds = lds0 + slot_a * C::A_BYTES;
+        if (STEADY || k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds, a0, a1);
+        else dm.template issue_a<true>(g, k_begin + ia, lds, a0, a1);
+    }
+}
+
+// The first requests of a segment on the LDS-DMA path: the batches that stages before the first would have
+// requested, all but the last (that one goes out in the MAC loop's first trip).  The ring must be free: no
+// wave may still read operands of the previous segment.  Called either at the start of the MAC loop or -
+// for the segment after the current one - before the current tile's fix-up and epilogue, so that the
+// first loads travel while the tile is stored.
+template <class C>
+__device__ __forceinline__ void mac_prefetch(const GemmArgs& g, int m0, int n0, int k_begin, int k_end, unsigned char* smem, const DmaMap<C>& dm) {
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_byte*)smem;
+    const int nk = k_end - k_begin, full_k = g.K / C::BK;
+#pragma unroll
+    for (int j = -C::NSA; j <= -2; j++)
+        issue_requests<C, false>(g, dm, lds0, k_begin, nk, full_k, j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
+}
+
 // MAC loop of one segment (Algorithm 1's MAC-loop call): k-iterations [k_begin, k_end) of one tile.
 //
 // Software pipeline of the LDS-DMA path.  Stage s (one k-iteration) lives in A ring slot s % NSA and
@@ -482,10 +523,17 @@ __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const un
 // so (1) stage i's slots can be refilled at once (with stages i+NSB / i+NSA), (2) the operands of
 // stage i+1's first k-step are read while the matrix cores still work on stage i's last one, and
 // (3) the time a wave spends at the barrier is covered by matrix-core work already queued.
+// prefetched / stores_in_flight (LDS-DMA path only): prefetched says that mac_prefetch has already been
+// called for this segment; stores_in_flight that this wave has since issued exactly C::EPILOGUE_STORES (or
+// more) other vector-memory instructions, which the first wait may leave in flight.  (The per-tile
+// addressing is worked out again here rather than kept from the prefetch: kept in registers across the
+// epilogue it gets spilled, and a reload pending at the loop's entry makes the compiler wait for every
+// outstanding load inside the steady-state trips.)
 template <class C, bool ALIGNED, bool TR>
 __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int k_begin, int k_end,
                                          unsigned char* smem, const FragMap<C>& fm,
-                                         typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI]) {
+                                         typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI],
+                                         bool prefetched, bool stores_in_flight) {
     const int nk = k_end - k_begin;
     if (C::DIRECT && ALIGNED) {
         static_assert(!C::DIRECT || C::KK % 2 == 0, "operand double buffering assumes an even number of k-steps");
@@ -493,30 +541,12 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         const int full_k = g.K / C::BK;             // iterations below this index are entirely inside K
         DmaMap<C> dm;
         dm.init(g, m0, n0);
+        if (!prefetched) mac_prefetch<C>(g, m0, n0, k_begin, k_end, smem, dm);
         // request batch j (issued after the barrier of stage j): B tile of stage j+NSB, then A tile of
         // stage j+NSA, into the slots of stage j; step / steps select a slice of the batch
         auto issue_batch = [&](int j, int slot_a, int slot_b, int step, int steps, auto steady) {
-            // steady: the caller knows that both stages exist and lie entirely inside K
-            constexpr bool STEADY = decltype(steady)::value;
-            const int ib = j + C::NSB, ia = j + C::NSA;
-            const int q0 = step * C::LPS / steps, q1 = (step + 1) * C::LPS / steps;
-            const int b0 = q0 < C::B_LD ? q0 : C::B_LD, b1 = q1 < C::B_LD ? q1 : C::B_LD;
-            const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
-            if ((STEADY || (ib >= 0 && ib < nk)) && b1 > b0) {
-                const uint32_t lds = lds0 + C::B_RING + slot_b * C::B_BYTES;
-                if (STEADY || k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
-                else dm.template issue_b<true>(g, k_begin + ib, lds, b0, b1);
-            }
-            if ((STEADY || (ia >= 0 && ia < nk)) && a1 > a0) {
-                const uint32_t lds = lds0 + slot_a * C::A_BYTES;
-                if (STEADY || k_begin + ia < full_k) dm.template issue_a<false>(g, k_begin + ia, lds, a0, a1);
-                else dm.template issue_a<true>(g, k_begin + ia, lds, a0, a1);
-            }
+            issue_requests<C, decltype(steady)::value>(g, dm, lds0, k_begin, nk, full_k, j, slot_a, slot_b, step, steps);
         };
-        // the batches that stages before the first would have requested, all but the last
-#pragma unroll
-        for (int j = -C::NSA; j <= -2; j++)
-            issue_batch(j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1, std::false_type());
         Frags<C> f[2];
         int ca = C::NSA - 1, cb = C::NSB - 1;        // ring slots of stage i (i = -1: the slots batch -1 fills)
         // one trip = [barrier that hands over stage i+1] [operands of stage i+1's first k-step]
@@ -563,6 +593,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
                 static_assert(!C::FINE || NEXT >= 0, "known at compile time under PIN_ORDER");
                 if (NEXT) {
                     if (STEADY) wait_vmcnt<C::in_flight(C::NSA - 1)>();
+                    else if (FIRST && stores_in_flight) wait_stage<C, C::NSA - 1, C::EPILOGUE_STORES>(nk - 2 - i);
                     else wait_stage<C, C::NSA - 1>(nk - 2 - i);
                     __syncthreads();
                 }
@@ -580,6 +611,7 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
             }
             if (has_next) {
                 if (STEADY) wait_vmcnt<C::in_flight(C::NSA - 1)>();
+                else if (FIRST && stores_in_flight) wait_stage<C, C::NSA - 1, C::EPILOGUE_STORES>(nk - 2 - i);
                 else wait_stage<C, C::NSA - 1>(nk - 2 - i);   // stage i+1 has landed (this wave's share)
                 __syncthreads();                         // ... and everybody's; stage i's slots are free
                 f[0].load(a_next, b_next, fm, 0);
@@ -910,11 +942,10 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             it = first_full; it_end = last_full;     // whole tiles (may be none)
         }
     }
-
-    while (true) {
+    // The next segment of this workgroup: tile index, k-iterations and the tile's origin; false when the work is done.
+    auto next_segment = [&](int& tile, int& k_begin, int& k_end, int& m0, int& n0) -> bool {
         if (it >= it_end) { it = next_b; it_end = next_e; next_b = last_b; next_e = last_e; last_b = last_e; }
         if (it >= it_end) { it = next_b; it_end = next_e; next_b = last_b; next_e = last_e; last_b = last_e; }
-        int tile, k_begin, k_end;
         const bool dp_now = dp_tile < g.tiles && (g.dp_first || it >= it_end);
         if (!dp_now && it < it_end) {            // Algorithm 1: cut the share at tile boundaries
             tile = (int)((uint32_t)it / (uint32_t)g.ipt);
@@ -927,7 +958,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             tile = dp_tile; k_begin = 0; k_end = g.ipt;
             dp_tile += g.grid;
         } else {
-            break;
+            return false;
         }
         int tm, tn;
         if (g.tile_order == SK_ORDER_ROW_MAJOR) {
@@ -941,22 +972,22 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             tn = (int)(within / rows);
             tm = (int)band * SK_GROUP_ROWS + (int)(within - (uint32_t)tn * rows);
         }
-        const int m0 = tm * C::BM, n0 = tn * C::BN;
+        m0 = tm * C::BM;
+        n0 = tn * C::BN;
+        return true;
+    };
 
-        Acc acc[C::MI][C::NI];
-#pragma unroll
-        for (int mi = 0; mi < C::MI; mi++)
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
-        mac_loop<C, ALIGNED, TR>(g, m0, n0, k_begin, k_end, smem, fm, acc);
-
+    // Fix-up and epilogue of one finished segment.  Returns true if every wave has issued exactly the
+    // stores of an unsplit interior tile (C::EPILOGUE_STORES for 16-bit outputs, more for fp32) and no
+    // other vector-memory instruction.
+    auto finish_segment = [&](int tile, int k_begin, int k_end, int m0, int n0, Acc (&acc)[C::MI][C::NI]) -> bool {
         if (ATOMIC) {
             int row0 = m0 + wm * C::WTM + 4 * (lane / C::MF), col0 = n0 + wn * C::WTN + lane % C::MF;
             asm volatile("" : "+v"(row0), "+v"(col0));
             const bool partial = k_begin > 0 || k_end < g.ipt;
             if (m0 + C::BM > g.M || n0 + C::BN > g.N) add_to_image<C, true>(g, row0, col0, partial, acc);
             else add_to_image<C, false>(g, row0, col0, partial, acc);
-            continue;
+            return false;
         }
 
         // ---- fix-up
@@ -1009,7 +1040,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             __syncthreads();
             if (tid == 0)
                 __hip_atomic_store(g.flags + (size_t)x * (SK_FLAG_STRIDE / 4), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            continue;
+            return false;
         }
         int n_contrib = 0;
         ptrdiff_t part_stride = slot_stride;
@@ -1041,6 +1072,35 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             if (edge) reduce_and_store<C, SK_F32, true, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
             else reduce_and_store<C, SK_F32, false, TR>(g, row0, col0, part0, n_contrib, part_stride, acc);
         }
+        return TR && !split && !edge;
+    };
+
+    // On the LDS-DMA path the first requests of the next segment go out before the current tile's
+    // fix-up and epilogue (the ring is free once the MAC loop has ended): the loads travel while the
+    // tile is stored, and the first wait of the next MAC loop leaves the epilogue's stores in flight.
+    constexpr bool PREFETCH = C::DIRECT && ALIGNED;
+    int tile, k_begin, k_end, m0, n0;
+    bool have = next_segment(tile, k_begin, k_end, m0, n0);
+    bool prefetched = false, stores_in_flight = false;
+    while (have) {
+        Acc acc[C::MI][C::NI];
+#pragma unroll
+        for (int mi = 0; mi < C::MI; mi++)
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
+        mac_loop<C, ALIGNED, TR>(g, m0, n0, k_begin, k_end, smem, fm, acc, prefetched, stores_in_flight);
+
+        // this segment's numbers for the fix-up and the epilogue; then look ahead
+        const int cur_tile = tile, cur_k_begin = k_begin, cur_k_end = k_end, cur_m0 = m0, cur_n0 = n0;
+        have = next_segment(tile, k_begin, k_end, m0, n0);
+        prefetched = PREFETCH && have;
+        stores_in_flight = false;
+        if (prefetched) {
+            DmaMap<C> ahead;
+            ahead.init(g, m0, n0);
+            mac_prefetch<C>(g, m0, n0, k_begin, k_end, smem, ahead);
+        }
+        stores_in_flight = finish_segment(cur_tile, cur_k_begin, cur_k_end, cur_m0, cur_n0, acc) && prefetched;
     }
 }
 

@@ -98,6 +98,33 @@ def test_alternative_wave_layouts_integer_exact(variant, blk):
     _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_SK1_DP, blk, grid=24, variant=variant)
 
 
+@pytest.mark.parametrize("blk,variant", [((128, 128, 64), 0), ((128, 128, 64), 1), ((256, 256, 64), 3), ((256, 256, 64), 1),
+                                         ((256, 128, 64), 0), ((32, 128, 64), 0), ((16, 128, 64), 0), ((128, 128, 32), 0)])
+def test_many_interior_tiles_per_workgroup_short_k(blk, variant):
+    # eight whole interior tiles per workgroup, one after the other, with 1, 2, 3 and 5 k-iterations each: the first
+    # requests of a tile go out before the previous tile's epilogue, and the first wait of its MAC loop leaves
+    # that epilogue's stores in flight - for every depth of the start-up of the ring, 16-bit and fp32 output
+    M, N = 4 * blk[0], 16 * blk[1]
+    for iters in (1, 2, 3, 5):
+        K = iters * blk[2]
+        A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 90 + iters)
+        ref = G.gemm_fp64(A, B, G.BF16)
+        for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK2_DP):
+            _run_and_compare(A, B, inputs.BF16, policy, blk, grid=8, out_dtype=sk.SK_F32, ref=ref, exact=True, variant=variant, launches=2)
+        _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_DP, blk, grid=8, ref=ref, variant=variant)            # bf16 output
+
+
+@pytest.mark.parametrize("blk,variant", [((256, 256, 128), 1), ((256, 256, 128), 3), ((128, 256, 128), 0)])
+def test_many_interior_tiles_per_workgroup_short_k_fp8(blk, variant):
+    M, N = 4 * blk[0], 8 * blk[1]
+    for iters in (1, 2, 3, 5):
+        K = iters * blk[2]
+        A, B = inputs.small_int_pair(M, N, K, inputs.E4M3, 95 + iters)
+        ref = G.gemm_fp64(A, B, G.E4M3)
+        _run_and_compare(A, B, inputs.E4M3, sk.SK_POLICY_DP, blk, grid=8, out_dtype=sk.SK_F32, ref=ref, exact=True, variant=variant, launches=2)
+        _run_and_compare(A, B, inputs.E4M3, sk.SK_POLICY_SK1_DP, blk, grid=8, ref=ref, variant=variant)        # bf16 output
+
+
 @pytest.mark.parametrize("shape", [(77, 101, 203), (1, 64, 16), (5, 7, 3), (130, 129, 1), (300, 8, 2049), (16, 264, 520)])
 def test_ragged_and_unaligned_shapes(shape):
     M, N, K = shape
