@@ -524,3 +524,46 @@ def test_sweep_then_selector_on_first_sizes_and_two_skinny_ones(tmp_path):
             assert want & ~sel.candidates(r) == 0
     finally:
         sel.close()
+
+
+# ---- seeded random configurations: everything against everything --------------------------------------------------
+
+def _random_cases(n, seed):
+    import random
+    rng = random.Random(seed)
+    tiles16 = [(128, 128, 32), (128, 128, 64), (256, 128, 64), (256, 256, 64), (64, 128, 64), (32, 128, 64), (16, 128, 64)]
+    cases = []
+    for _ in range(n):
+        fp8 = rng.random() < 0.2
+        blk = rng.choice([(256, 256, 128), (128, 256, 128)]) if fp8 else rng.choice(tiles16)
+        tiles_m, tiles_n, iters = rng.randint(1, 5), rng.randint(1, 6), rng.randint(1, 9)
+        aligned = rng.random() < 0.7
+        M = tiles_m * blk[0] - rng.choice([0, 0, 1, 17, blk[0] // 2])
+        N = tiles_n * blk[1] - (rng.choice([0, 0, 8, 24, 64]) if aligned else rng.choice([1, 3, 13]))
+        K = iters * blk[2] - (rng.choice([0, 0, 8, 16, 40]) if aligned else rng.choice([1, 5, 11]))
+        M, N, K = max(M, 1), max(N, 8 if aligned else 1), max(K, 8 if aligned else 1)
+        grid = rng.choice([4, 8, 13, 24, 64, 256])
+        variant = rng.choice([0, 0, 1, 3])
+        cases.append(dict(M=M, N=N, K=K, blk=blk, dtype=inputs.E4M3 if fp8 else rng.choice([inputs.BF16, inputs.F16]),
+                          policy=rng.randrange(8), grid=grid, out_f32=rng.random() < 0.6, variant=variant,
+                          atomic=(not fp8 or blk[0] == 128) and variant == 0 and blk != (256, 256, 32) and rng.random() < 0.15,
+                          dp_first=rng.random() < 0.2, k_aligned=rng.random() < 0.75, seed=rng.randrange(1 << 20)))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_seeded_random_configurations_integer_exact(chunk):
+    # 20 configurations per chunk: tile family, wave layout, policy, grid, ragged or unaligned sizes, output type, fix-up
+    # mode, batch order and segment order drawn together; integer-valued inputs, so every result must be exact
+    for c in _random_cases(120, 2024)[chunk * 20:(chunk + 1) * 20]:
+        A, B = inputs.small_int_pair(c["M"], c["N"], c["K"], c["dtype"], c["seed"])
+        ref = G.gemm_fp64(A, B, ODT[c["dtype"]])
+        out = sk.SK_F32 if c["out_f32"] else None
+        fixup = sk.SK_FIXUP_ATOMIC if c["atomic"] else sk.SK_FIXUP_FLAGS
+        if out is None:
+            # 16-bit outputs hold these integers exactly as long as they stay below 2^8 (bf16) / 2^11 (fp16): compare with a tolerance instead
+            _run_and_compare(A, B, c["dtype"], c["policy"], c["blk"], grid=c["grid"], ref=ref, fixup=fixup, launches=2,
+                             dp_first=c["dp_first"], k_aligned=c["k_aligned"], variant=c["variant"])
+        else:
+            _run_and_compare(A, B, c["dtype"], c["policy"], c["blk"], grid=c["grid"], out_dtype=out, ref=ref, exact=True, fixup=fixup,
+                             launches=2, dp_first=c["dp_first"], k_aligned=c["k_aligned"], variant=c["variant"])
