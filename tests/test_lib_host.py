@@ -25,6 +25,22 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_public_header_is_plain_c_and_links(tmp_path):
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    exe = str(tmp_path / "header_is_c")
+    lib_dir = os.path.dirname(sk.binding.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "host", "header_is_c.c"), "-L", lib_dir, "-l:libstreamk.so", "-Wl,-rpath," + lib_dir,
+           "-Wl,--allow-shlib-undefined", "-o", exe]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout
+    res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert res.returncode == 0 and res.stdout.strip().endswith("ok"), (res.returncode, res.stdout[-2000:])
+
+
 def _plan_pair(M, N, K, policy, blk, g, order=None, dp_first=False, k_aligned=None):
     p = sk.sk_plan(M, N, K, policy, blk, g, tile_order=order)
     try:
