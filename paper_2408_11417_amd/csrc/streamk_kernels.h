@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 #include <atomic>
 #include <type_traits>
+#include <utility>
 #include "streamk_internal.h"
 
 
@@ -700,6 +701,12 @@ __device__ __forceinline__ void wait_flags(const GemmArgs& g, int first, int cou
     }
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>)
+template <int N, class F, int... I>
+__device__ __forceinline__ void for_each_below_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>()), ...); }
+template <int N, class F>
+__device__ __forceinline__ void for_each_below(F&& f) { for_each_below_impl<N>(f, std::make_integer_sequence<int, N>()); }
+
 // blk += this block's share of the parked partial tiles src, src + stride, ... (`count` of them), in
 // that order, GB contributors per round trip (GB * ACC registers of loads in flight).
 template <class C, int GB>
@@ -764,7 +771,11 @@ __device__ __forceinline__ void add_partials(typename Mfma<C::DT, C::MF>::Acc (&
     };
     int c = 0;
     for (; c + G <= count; c += G, src += G * stride) add_group(src, std::integral_constant<int, G>());
-    for (; c < count; c++, src += stride) add_group(src, std::integral_constant<int, 1>());
+    // the 1 .. G-1 contributors left over: one round trip for all of them (the order of the additions is
+    // the same whatever the grouping)
+    for_each_below<G>([&](auto r) {
+        if (decltype(r)::value > 0 && count - c == decltype(r)::value) add_group(src, std::integral_constant<int, decltype(r)::value < 1 ? 1 : decltype(r)::value>());
+    });
     }
 }
 
