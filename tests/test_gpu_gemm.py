@@ -427,6 +427,20 @@ def test_tiles_shared_by_many_workgroups(blk, shape):
         r.close()
 
 
+@pytest.mark.parametrize("blk", [(16, 128, 64), (32, 128, 64), (64, 128, 64), (128, 128, 64)])
+def test_every_small_contributor_count(blk):
+    # 1 ... 9 contributors per tile: the owner fetches them in groups (2 to 8 per round trip, by tile) and
+    # the ones left over together - every group size and every remainder occurs
+    bm, bn, bk = blk
+    for c in range(1, 10):
+        M, N, K = bm, 2 * bn, bk * 3 * (c + 1)
+        A, B = inputs.small_int_pair(M, N, K, inputs.BF16, 50 + c)
+        ref = G.gemm_fp64(A, B, G.BF16)
+        _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_ALL_SK, blk, grid=2 * (c + 1), out_dtype=sk.SK_F32, ref=ref, exact=True, launches=2)
+        _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_ALL_SK, blk, grid=2 * (c + 1), out_dtype=sk.SK_BF16, ref=ref)     # sums beyond 256 round in bf16
+        _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_ALL_SK, blk, grid=2 * (c + 1), out_dtype=sk.SK_F32, ref=ref, exact=True, k_aligned=False)
+
+
 @pytest.mark.parametrize("blk", [(128, 128, 64), (256, 128, 64), (256, 256, 64), (32, 128, 64)])
 def test_data_parallel_batches_first(blk):
     # Sec. 3.2's earlier hybrid: the same work, data-parallel tiles before the Stream-K iterations, under both fix-ups
