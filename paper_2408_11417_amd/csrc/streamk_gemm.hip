@@ -156,6 +156,11 @@ int launch_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, vo
     g.dp_first = plan->dp_first;
     g.k_aligned = plan->k_aligned;
     g.xcd_remap = h.xcd_remap;
+    g.div_ipt = sk_make_fast_div((uint32_t)h.iters_per_tile);
+    g.div_ipw = sk_make_fast_div((uint32_t)h.iters_per_wg);
+    g.div_tiles_n = sk_make_fast_div((uint32_t)h.tiles_n);
+    g.div_band = sk_make_fast_div((uint32_t)(SK_GROUP_ROWS * h.tiles_n));
+    g.div_last_rows = sk_make_fast_div((uint32_t)(h.tiles_m % SK_GROUP_ROWS));
     if (atomic) {
         // Algorithm 1's atomic accumulation needs C to start at zero: clear the image in-stream, accumulate, convert
         const size_t n = (size_t)h.M * (size_t)h.N;

@@ -27,6 +27,21 @@ inline size_t sk_ws_partials_offset(int grid) { return ((size_t)grid + 1) * SK_F
 // 256 partial tiles of 256 x 256 fp32 (the largest tile), i.e. every plan on the default grid.
 constexpr size_t SK_STATIC_WORKSPACE_MAX = (256 + 1) * SK_FLAG_STRIDE + 384 + (size_t)256 * 256 * 256 * 4;
 
+// Division of a number below 2^31 by a divisor that is fixed for a launch: with shift = 31 + ceil(log2 d)
+// and mul = ceil(2^shift / d) (which fits 32 bits), n / d == (n * mul) >> shift for every n < 2^31, because
+// the error n * (mul * d - 2^shift) stays below 2^shift.  The kernels' index arithmetic (Algorithm 1's
+// iteration -> tile and tile -> workgroup maps) sits ahead of a workgroup's first load and inside the
+// fix-up chain, and a division by a run-time value costs about 300 cycles of dependent instructions there.
+struct sk_fast_div { uint32_t mul, shift; };
+inline sk_fast_div sk_make_fast_div(uint32_t d) {
+    if (d == 0) return sk_fast_div{0u, 0u};          // never divided by (e.g. no Stream-K iterations)
+    uint32_t log2_up = 0;
+    while ((1ull << log2_up) < d) log2_up++;
+    const uint32_t shift = 31 + log2_up;
+    return sk_fast_div{(uint32_t)(((1ull << shift) + d - 1) / d), shift};
+}
+inline uint32_t sk_fast_div_apply(uint32_t n, sk_fast_div f) { return (uint32_t)(((uint64_t)n * f.mul) >> f.shift); }
+
 // Does the GEMM launcher hold a kernel for this configuration?
 bool sk_kernel_available(int in_dtype, int blk_m, int blk_n, int blk_k);
 // Bytes of the fp32 image of D that the atomic fix-up accumulates into (0 if D itself serves).

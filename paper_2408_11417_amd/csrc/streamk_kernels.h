@@ -55,7 +55,11 @@ struct GemmArgs {
     int k_aligned;         // 1: a workgroup runs the whole tiles of its Stream-K range first, then the head of its last
                            //    tile (k from 0), then the tail of its first one, and the workgroup holding a tile's
                            //    last iteration reduces and stores it
+    // divisors of the index arithmetic: ipt, ipw, tiles_n, SK_GROUP_ROWS * tiles_n, rows of the last (short) band
+    sk_fast_div div_ipt, div_ipw, div_tiles_n, div_band, div_last_rows;
 };
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, sk_fast_div f) { return (uint32_t)(((uint64_t)n * f.mul) >> f.shift); }
 
 // ---- matrix-core wrappers ---------------------------------------------------------------------
 // One instruction multiplies an MF x KM block (first operand) by a KM x MF block (second operand).
@@ -945,8 +949,8 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
     // pieces before it in k have long been parked.
     int next_b = it_end, next_e = it_end, last_b = it_end, last_e = it_end;     // the sub-ranges after [it, it_end)
     if (g.k_aligned && it < it_end) {
-        const int first_full = (int)(((uint32_t)it + (uint32_t)g.ipt - 1) / (uint32_t)g.ipt) * g.ipt;
-        const int last_full = (int)((uint32_t)it_end / (uint32_t)g.ipt) * g.ipt;
+        const int first_full = (int)fast_div((uint32_t)it + (uint32_t)g.ipt - 1, g.div_ipt) * g.ipt;
+        const int last_full = (int)fast_div((uint32_t)it_end, g.div_ipt) * g.ipt;
         if (first_full <= last_full) {
             next_b = last_full; next_e = it_end;     // head piece (may be empty)
             last_b = it; last_e = first_full;        // tail piece (may be empty)
@@ -959,7 +963,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         if (it >= it_end) { it = next_b; it_end = next_e; next_b = last_b; next_e = last_e; last_b = last_e; }
         const bool dp_now = dp_tile < g.tiles && (g.dp_first || it >= it_end);
         if (!dp_now && it < it_end) {            // Algorithm 1: cut the share at tile boundaries
-            tile = (int)((uint32_t)it / (uint32_t)g.ipt);
+            tile = (int)fast_div((uint32_t)it, g.div_ipt);
             const int tile_first = tile * g.ipt;
             k_begin = it - tile_first;
             const int stop = it_end < tile_first + g.ipt ? it_end : tile_first + g.ipt;
@@ -973,14 +977,14 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         }
         int tm, tn;
         if (g.tile_order == SK_ORDER_ROW_MAJOR) {
-            tm = (int)((uint32_t)tile / (uint32_t)g.tiles_n);
+            tm = (int)fast_div((uint32_t)tile, g.div_tiles_n);
             tn = tile - tm * g.tiles_n;
         } else {                                 // bands of 8 tile rows, walked column by column
             const uint32_t per_band = (uint32_t)(SK_GROUP_ROWS * g.tiles_n);
-            const uint32_t band = (uint32_t)tile / per_band, within = (uint32_t)tile - band * per_band;
+            const uint32_t band = fast_div((uint32_t)tile, g.div_band), within = (uint32_t)tile - band * per_band;
             const int left = g.tiles_m - (int)band * SK_GROUP_ROWS;
             const uint32_t rows = (uint32_t)(left < SK_GROUP_ROWS ? left : SK_GROUP_ROWS);
-            tn = (int)(within / rows);
+            tn = (int)(left < SK_GROUP_ROWS ? fast_div(within, g.div_last_rows) : within / (uint32_t)SK_GROUP_ROWS);
             tm = (int)band * SK_GROUP_ROWS + (int)(within - (uint32_t)tn * rows);
         }
         m0 = tm * C::BM;
@@ -1013,8 +1017,8 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         const int dir = g.k_aligned ? -1 : 1;
         int j = 0, n_all = 0;                                           // distance from the tile's owner, the tile's number of contributors
         if (split) {                                                    // (only split tiles; ipw is 0 in a plan without Stream-K work)
-            const int first_wg = (int)((uint32_t)(tile * g.ipt) / (uint32_t)g.ipw);
-            const int last_wg = (int)((uint32_t)(tile * g.ipt + g.ipt - 1) / (uint32_t)g.ipw);
+            const int first_wg = (int)fast_div((uint32_t)(tile * g.ipt), g.div_ipw);
+            const int last_wg = (int)fast_div((uint32_t)(tile * g.ipt + g.ipt - 1), g.div_ipw);
             n_all = last_wg - first_wg;
             j = g.k_aligned ? last_wg - x : x - first_wg;
         }
@@ -1060,7 +1064,7 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
             // two levels, their group leaders.  Wait for all of them; the epilogue adds their
             // partials in a fixed order, so the result does not depend on timing.
             const int step = two_level ? SK_TREE_GROUP : 1;
-            n_contrib = (n_all + step - 1) / step;
+            n_contrib = two_level ? (n_all + SK_TREE_GROUP - 1) / SK_TREE_GROUP : n_all;
             part_stride *= step;
             if (wave == 0) wait_flags(g, x + dir, n_contrib, step * dir);
             __syncthreads();

@@ -8,6 +8,7 @@
 #include <cstring>
 #include <vector>
 #include "streamk.h"
+#include "streamk_internal.h"
 
 // the planner asks the GEMM launcher whether a kernel exists; this build has no launcher
 bool sk_kernel_available(int, int, int, int) { return false; }
@@ -94,8 +95,31 @@ static int bloom_case(FILE* f) {
     return 0;
 }
 
+// The multiply-shift division the kernels use for their index arithmetic equals n / d for every divisor and
+// every numerator below 2^31 (checked: all small divisors and seeded random ones, numerators at and next to
+// every multiple boundary that matters and at the top of the range).
+static int fast_div_case() {
+    uint64_t state = 12345;
+    auto next = [&]() { state = state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(state >> 33); };
+    for (int c = 0; c < 70000; c++) {
+        const uint32_t d = c < 5000 ? (uint32_t)c + 1 : c < 5032 ? 1u << (c - 5000) % 31 : 1 + next() % (1u << (1 + next() % 30));
+        const sk_fast_div f = sk_make_fast_div(d);
+        if (f.shift < 31 || f.shift > 62 || (uint64_t)f.mul * d < (1ull << f.shift)) FAIL("bad constants for %u", d);
+        const uint32_t top = 0x7FFFFFFFu;
+        uint32_t ns[12] = {0, 1, d - 1, d, d + 1, top, top - 1, top / d * d, top / d * d - 1, next() & top, next() & top, (next() % 1024) * d + d - 1};
+        for (uint32_t n : ns) {
+            if (n > top) continue;
+            if (sk_fast_div_apply(n, f) != n / d) FAIL("%u / %u: got %u", n, d, sk_fast_div_apply(n, f));
+        }
+    }
+    const sk_fast_div zero = sk_make_fast_div(0);
+    if (zero.mul != 0 || zero.shift != 0) FAIL("divisor 0");
+    return 0;
+}
+
 int main(int argc, char** argv) {
     if (argc != 2) FAIL("usage: sanitizer_driver CASES");
+    if (fast_div_case()) return 1;
     FILE* f = fopen(argv[1], "r");
     if (!f) FAIL("cannot open %s", argv[1]);
     char kind[16];
