@@ -215,6 +215,13 @@ class Bench:
         roof.update(traffic=None if args.ascending else measured_traffic(self.name, sk.POLICY_NAMES[sel]),
                     algorithmic_bytes=alg_bytes, kernel="streamk_gemm_kernel", kernel_ms=round(kernel_ms, 5),
                     step_event_ms=round(step_ms, 5))
+        if self.hbm_bound:
+            # reported apart: the same launches on one operand set, which the 256 MB memory-side cache then serves
+            rotating, self.sets = self.sets, self.sets[:1]
+            hot_ms = self.time_policy(sel, 10, steps)
+            self.sets = rotating
+            roof["hot_cache"] = {"kernel_ms": round(hot_ms, 5), "GBps": round(alg_bytes / (hot_ms * 1e-3) / 1e9, 1),
+                                 "note": "one operand set, B served by the memory-side cache; not the judged figure"}
         out = {"workload": self.c["label"], "M": self.M, "N": self.N, "K": self.K, "dtype": dtype_name,
                "tile": [self.info["blk_m"], self.info["blk_n"], self.info["blk_k"]], "grid": self.info["grid"],
                "value": round(self.flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "ms_per_step": round(ms_per_step, 5),
@@ -306,6 +313,36 @@ def mfma_peak():
         out[name] = res
     out["unit"] = "TFLOP/s"
     out["kernel"] = "mfma_peak_kernel: 256 workgroups x 4 waves, 16 independent 32x32 matrix-core instructions per trip, operands in registers"
+    return out
+
+
+def bloom_query_timing(bloom, with_oracle):
+    """Nanoseconds per filter query on one host thread: the library's bloom_query_many over 200 000 seeded
+    keys (one C call, arrays marshalled beforehand) and - as part of the CPU-baseline leg only - the
+    Python oracle's query over 2000 of them against filters of the same parameters and contents."""
+    import ctypes
+    import paper_2408_11417_amd as sk
+    rng = np.random.default_rng(5)
+    n = 200000
+    sizes = np.ascontiguousarray(rng.integers(1, 1 << 20, size=(n, 3), dtype=np.uint32))
+    masks = np.zeros(n, dtype=np.uint32)
+    lib = sk.binding._lib
+    ptr = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))
+    lib.bloom_query_many(bloom, ptr(sizes), ctypes.c_size_t(1000), ptr(masks))
+    t0 = time.perf_counter()
+    rc = lib.bloom_query_many(bloom, ptr(sizes), ctypes.c_size_t(n), ptr(masks))
+    dt_lib = time.perf_counter() - t0
+    assert rc == sk.SK_OK
+    out = {"library_ns_per_query": round(dt_lib / n * 1e9, 1), "queries": n, "threads": 1,
+           "filters": "7 x 95 872 bits, 7 probes (the sweep's build split, or one record without a sweep)"}
+    if with_oracle:
+        from oracle import bloom as Bm
+        o = Bm.build([(3, 5, 7, 0x7F)])
+        m = 2000
+        t0 = time.perf_counter()
+        for i in range(m):
+            o.query(int(sizes[i, 0]), int(sizes[i, 1]), int(sizes[i, 2]))
+        out["oracle_python_ns_per_query"] = round((time.perf_counter() - t0) / m * 1e9, 1)
     return out
 
 
@@ -405,6 +442,11 @@ def main():
     if own_tile:
         out["library_default_tile"] = own_tile
     cpu = None if args.no_cpu_baseline else head.cpu_baseline()
+    if not args.only or not args.no_cpu_baseline:
+        own = None if sel is not None else sk.bloom_build([(3, 5, 7, 0x7F)])
+        out["bloom_query"] = bloom_query_timing(sel.bloom if sel is not None else own, not args.no_cpu_baseline)
+        if own is not None:
+            sk.bloom_destroy(own)
     head.close()
     del head
     torch.cuda.empty_cache()
