@@ -156,6 +156,7 @@ int launch_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, vo
     g.dp_first = plan->dp_first;
     g.k_aligned = plan->k_aligned;
     g.xcd_remap = h.xcd_remap;
+    g.stream_b = h.tiles_m == 1;
     g.div_ipt = sk_make_fast_div((uint32_t)h.iters_per_tile);
     g.div_ipw = sk_make_fast_div((uint32_t)h.iters_per_wg);
     g.div_tiles_n = sk_make_fast_div((uint32_t)h.tiles_n);

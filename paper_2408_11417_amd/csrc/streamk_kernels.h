@@ -55,6 +55,7 @@ struct GemmArgs {
     int k_aligned;         // 1: a workgroup runs the whole tiles of its Stream-K range first, then the head of its last
                            //    tile (k from 0), then the tail of its first one, and the workgroup holding a tile's
                            //    last iteration reduces and stores it
+    int stream_b;          // 1: B is read exactly once (one row of tiles): the low tiles request it non-temporally
     // divisors of the index arithmetic: ipt, ipw, tiles_n, SK_GROUP_ROWS * tiles_n, rows of the last (short) band
     sk_fast_div div_ipt, div_ipw, div_tiles_n, div_band, div_last_rows;
 };
@@ -152,6 +153,10 @@ struct Cfg {
     // a wave that has a SIMD to itself keeps the matrix-core pipe fed while its memory instructions
     // queue up (needs the two operand sets of PIN_ORDER).
     static constexpr bool FINE = FINE_ != 0;
+    // the tiles of at most 64 rows (HBM-bound shapes) can request B non-temporally, decided per launch
+    // (GemmArgs::stream_b); the larger tiles re-use B blocks through the L2 caches and their request code
+    // sits in the instruction-by-instruction loop, so they carry no such switch
+    static constexpr bool MAY_STREAM_B = BM <= 64;
     static_assert(!FINE || PIN_ORDER, "the instruction-by-instruction order needs two operand sets");
     // register-staged path: room to hold the next stage's pieces (4 registers each) during the matrix-core work
     static constexpr bool STAGE_AHEAD = NW >= 8 ? 2 * FRAG_REGS + ACC_REGS + 4 * (CA + CB) + 64 <= 256 : 2 * FRAG_REGS + 4 * (CA + CB) + 64 <= 224;
@@ -205,6 +210,11 @@ static __device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
 // reads it), and naming a reserved register in a clobber list is rejected as undefined behaviour.
 __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base));
+}
+// The same load marked non-temporal: for data that is read exactly once (the B operand of a plan with a
+// single row of tiles), so that the stream does not displace what the L2 caches are needed for.
+__device__ __forceinline__ void lds_dma16_nt(const void* base, uint32_t byte_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(byte_off), "s"(base), "s"(lds_base));
 }
 __device__ __forceinline__ void lds_dma16_ptr(const void* gptr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base));
@@ -335,7 +345,7 @@ template <class C> struct DmaMap {
             }
         }
     }
-    template <bool TAIL> __device__ __forceinline__ void issue_b(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::B_LD) const {
+    template <bool TAIL, bool NT = false> __device__ __forceinline__ void issue_b(const GemmArgs& g, int kit, uint32_t lds, int j0 = 0, int j1 = C::B_LD) const {
         const int lane = threadIdx.x % 64;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
         const char* B = static_cast<const char*>(g.B) + (size_t)((uint32_t)kit * (uint32_t)(C::BK * C::ES)) * (uint32_t)g.N;
@@ -343,7 +353,8 @@ template <class C> struct DmaMap {
         for (int j = 0; j < C::B_LD; j++) {
             if (j < j0 || j >= j1) continue;
             if (!TAIL) {
-                lds_dma16(B, b_off[j], lds + (j * C::NW + wave) * 1024);
+                if (NT) lds_dma16_nt(B, b_off[j], lds + (j * C::NW + wave) * 1024);
+                else lds_dma16(B, b_off[j], lds + (j * C::NW + wave) * 1024);
             } else {
                 const int p = (j * C::NW + wave) * 64 + lane;
                 const char* src = kit * C::BK + p / C::CPB < g.K ? B + b_off[j] : reinterpret_cast<const char*>(g_zero_piece);
@@ -487,7 +498,7 @@ __device__ __forceinline__ void mac_stage(const unsigned char* a_stage, const un
 // Slice `step` of `steps` of request batch j of a segment (k-iterations k_begin .. k_begin + nk - 1 of a
 // tile): the B tile of stage j + NSB, then the A tile of stage j + NSA, into ring slots slot_b / slot_a.
 // STEADY: the caller knows that both stages exist and lie entirely inside K.
-template <class C, bool STEADY>
+template <class C, bool STEADY, bool NT>
 __device__ __forceinline__ void issue_requests(const GemmArgs& g, const DmaMap<C>& dm, uint32_t lds0, int k_begin, int nk, int full_k,
                                                int j, int slot_a, int slot_b, int step, int steps) {
     const int ib = j + C::NSB, ia = j + C::NSA;
@@ -496,8 +507,8 @@ __device__ __forceinline__ void issue_requests(const GemmArgs& g, const DmaMap<C
     const int a0 = q0 > C::B_LD ? q0 - C::B_LD : 0, a1 = q1 > C::B_LD ? q1 - C::B_LD : 0;
     if ((STEADY || (ib >= 0 && ib < nk)) && b1 > b0) {
         const uint32_t lds = lds0 + C::B_RING + slot_b * C::B_BYTES;
-        if (STEADY || k_begin + ib < full_k) dm.template issue_b<false>(g, k_begin + ib, lds, b0, b1);
-        else dm.template issue_b<true>(g, k_begin + ib, lds, b0, b1);
+        if (STEADY || k_begin + ib < full_k) dm.template issue_b<false, NT>(g, k_begin + ib, lds, b0, b1);
+        else dm.template issue_b<true, NT>(g, k_begin + ib, lds, b0, b1);
     }
     if ((STEADY || (ia >= 0 && ia < nk)) && a1 > a0) {
         const uint32_t lds = lds0 + slot_a * C::A_BYTES;
@@ -511,13 +522,13 @@ __device__ __forceinline__ void issue_requests(const GemmArgs& g, const DmaMap<C
 // wave may still read operands of the previous segment.  Called either at the start of the MAC loop or -
 // for the segment after the current one - before the current tile's fix-up and epilogue, so that the
 // first loads travel while the tile is stored.
-template <class C>
+template <class C, bool NT>
 __device__ __forceinline__ void mac_prefetch(const GemmArgs& g, int m0, int n0, int k_begin, int k_end, unsigned char* smem, const DmaMap<C>& dm) {
     const uint32_t lds0 = (uint32_t)(size_t)(lds_byte*)smem;
     const int nk = k_end - k_begin, full_k = g.K / C::BK;
 #pragma unroll
     for (int j = -C::NSA; j <= -2; j++)
-        issue_requests<C, false>(g, dm, lds0, k_begin, nk, full_k, j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
+        issue_requests<C, false, NT>(g, dm, lds0, k_begin, nk, full_k, j, (j + C::NSA) % C::NSA, (j + 2 * C::NSB) % C::NSB, 0, 1);
 }
 
 // MAC loop of one segment (Algorithm 1's MAC-loop call): k-iterations [k_begin, k_end) of one tile.
@@ -534,7 +545,7 @@ __device__ __forceinline__ void mac_prefetch(const GemmArgs& g, int m0, int n0, 
 // addressing is worked out again here rather than kept from the prefetch: kept in registers across the
 // epilogue it gets spilled, and a reload pending at the loop's entry makes the compiler wait for every
 // outstanding load inside the steady-state trips.)
-template <class C, bool ALIGNED, bool TR>
+template <class C, bool ALIGNED, bool TR, bool NT>
 __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int k_begin, int k_end,
                                          unsigned char* smem, const FragMap<C>& fm,
                                          typename Mfma<C::DT, C::MF>::Acc (&acc)[C::MI][C::NI],
@@ -546,11 +557,11 @@ __device__ __forceinline__ void mac_loop(const GemmArgs& g, int m0, int n0, int 
         const int full_k = g.K / C::BK;             // iterations below this index are entirely inside K
         DmaMap<C> dm;
         dm.init(g, m0, n0);
-        if (!prefetched) mac_prefetch<C>(g, m0, n0, k_begin, k_end, smem, dm);
+        if (!prefetched) mac_prefetch<C, NT>(g, m0, n0, k_begin, k_end, smem, dm);
         // request batch j (issued after the barrier of stage j): B tile of stage j+NSB, then A tile of
         // stage j+NSA, into the slots of stage j; step / steps select a slice of the batch
         auto issue_batch = [&](int j, int slot_a, int slot_b, int step, int steps, auto steady) {
-            issue_requests<C, decltype(steady)::value>(g, dm, lds0, k_begin, nk, full_k, j, slot_a, slot_b, step, steps);
+            issue_requests<C, decltype(steady)::value, NT>(g, dm, lds0, k_begin, nk, full_k, j, slot_a, slot_b, step, steps);
         };
         Frags<C> f[2];
         int ca = C::NSA - 1, cb = C::NSB - 1;        // ring slots of stage i (i = -1: the slots batch -1 fills)
@@ -1103,7 +1114,9 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         for (int mi = 0; mi < C::MI; mi++)
 #pragma unroll
             for (int ni = 0; ni < C::NI; ni++) acc[mi][ni] = Acc{};
-        mac_loop<C, ALIGNED, TR>(g, m0, n0, k_begin, k_end, smem, fm, acc, prefetched, stores_in_flight);
+        // B requested non-temporally or not: decided once per launch, two copies of the loop in the low tiles
+        if (C::MAY_STREAM_B && g.stream_b) mac_loop<C, ALIGNED, TR, C::MAY_STREAM_B>(g, m0, n0, k_begin, k_end, smem, fm, acc, prefetched, stores_in_flight);
+        else mac_loop<C, ALIGNED, TR, false>(g, m0, n0, k_begin, k_end, smem, fm, acc, prefetched, stores_in_flight);
 
         // this segment's numbers for the fix-up and the epilogue; then look ahead
         const int cur_tile = tile, cur_k_begin = k_begin, cur_k_end = k_end, cur_m0 = m0, cur_n0 = n0;
@@ -1113,7 +1126,8 @@ __global__ __launch_bounds__(C::THREADS) void streamk_gemm_kernel(GemmArgs g) {
         if (prefetched) {
             DmaMap<C> ahead;
             ahead.init(g, m0, n0);
-            mac_prefetch<C>(g, m0, n0, k_begin, k_end, smem, ahead);
+            if (C::MAY_STREAM_B && g.stream_b) mac_prefetch<C, C::MAY_STREAM_B>(g, m0, n0, k_begin, k_end, smem, ahead);
+            else mac_prefetch<C, false>(g, m0, n0, k_begin, k_end, smem, ahead);
         }
         stores_in_flight = finish_segment(cur_tile, cur_k_begin, cur_k_end, cur_m0, cur_n0, acc) && prefetched;
     }
