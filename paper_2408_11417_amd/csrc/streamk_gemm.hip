@@ -156,7 +156,11 @@ int launch_gemm(const void* A, const void* B, void* D, const sk_plan_t* plan, vo
     g.dp_first = plan->dp_first;
     g.k_aligned = plan->k_aligned;
     g.xcd_remap = h.xcd_remap;
-    g.stream_b = h.tiles_m == 1;
+    // B is requested non-temporally when it is read exactly once (one row of tiles) and is too large to be
+    // found in the 256 MB memory-side cache by a later launch anyway (at least half of it: 128 MiB).  Measured:
+    // 16 x 8192 x 8192 and 16 x 16384 x 4096 (128 MiB) 5 - 6 % faster, 16 x 4096 x 4096 and 32 x 8192 x 2048
+    // (32 MiB, served by the caches from launch to launch) 10 - 25 % slower with the hint.
+    g.stream_b = h.tiles_m == 1 && (size_t)h.K * (size_t)h.N * (h.in_dtype == SK_FP8_E4M3 ? 1 : 2) >= ((size_t)128 << 20);
     g.div_ipt = sk_make_fast_div((uint32_t)h.iters_per_tile);
     g.div_ipw = sk_make_fast_div((uint32_t)h.iters_per_wg);
     g.div_tiles_n = sk_make_fast_div((uint32_t)h.tiles_n);

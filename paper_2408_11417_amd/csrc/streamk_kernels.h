@@ -55,7 +55,7 @@ struct GemmArgs {
     int k_aligned;         // 1: a workgroup runs the whole tiles of its Stream-K range first, then the head of its last
                            //    tile (k from 0), then the tail of its first one, and the workgroup holding a tile's
                            //    last iteration reduces and stores it
-    int stream_b;          // 1: B is read exactly once (one row of tiles): the low tiles request it non-temporally
+    int stream_b;          // 1: B is read exactly once (one row of tiles) and is large: the low tiles request it non-temporally
     // divisors of the index arithmetic: ipt, ipw, tiles_n, SK_GROUP_ROWS * tiles_n, rows of the last (short) band
     sk_fast_div div_ipt, div_ipw, div_tiles_n, div_band, div_last_rows;
 };
@@ -211,8 +211,8 @@ static __device__ __align__(16) const unsigned char g_zero_piece[16] = {0};
 __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base));
 }
-// The same load marked non-temporal: for data that is read exactly once (the B operand of a plan with a
-// single row of tiles), so that the stream does not displace what the L2 caches are needed for.
+// The same load marked non-temporal: for data that is read exactly once and is too large for the caches
+// to hold until a later launch (the B operand of a plan with a single row of tiles, see the launcher).
 __device__ __forceinline__ void lds_dma16_nt(const void* base, uint32_t byte_off, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(byte_off), "s"(base), "s"(lds_base));
 }
