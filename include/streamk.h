@@ -257,6 +257,10 @@ int sk_plan_set_spin_limit(sk_plan_t* plan, uint32_t polls);
  * part of the device can wait for each other until the bounded wait gives up
  * (SK_ERR_TIMEOUT from sk_plan_check, D invalid).  Plans without split tiles and
  * SK_FIXUP_ATOMIC launches never wait and may overlap freely.
+ * Cache policy: a plan with a single row of tiles at most 64 rows high reads B
+ * exactly once; if B is also 128 MiB or more (too large to be found in the
+ * memory-side cache by a later launch), its loads carry the non-temporal hint.
+ * All other operand loads use the default policy.
  * Errors: INVALID_ARG, UNSUPPORTED (no kernel for tile + dtype + fix-up mode,
  * sizes beyond the kernels' 32-bit index range: M*K or K*N >= 2^31 elements,
  * M*N >= 2^32, or the grid cannot be co-resident while the plan has split
