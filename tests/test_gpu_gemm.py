@@ -225,6 +225,13 @@ def test_config3_skinny(M):
     for policy in (sk.SK_POLICY_DP, sk.SK_POLICY_SK1_DP, sk.SK_POLICY_ALL_SK):
         _run_and_compare(c["A"], c["B"], inputs.BF16, policy, None, 256, ref=ref)
     _run_and_compare(c["A"], c["B"], inputs.BF16, sk.SK_POLICY_ALL_SK, None, 256, out_dtype=sk.SK_F32, ref=ref)
+    if M == 16:
+        # B is 128 MiB and read once here: the launches above and these request it non-temporally; the
+        # lowest tile and the four-wave 64-row kernel take that path too
+        _run_and_compare(c["A"], c["B"], inputs.BF16, sk.SK_POLICY_ALL_SK, (16, 128, 64), 256, ref=ref)
+        _run_and_compare(c["A"], c["B"], inputs.BF16, sk.SK_POLICY_DP, (64, 128, 64), 256, ref=ref, variant=1)
+        A, B = inputs.small_int_pair(16, 8192, 8192, inputs.BF16, 77, lo=-2, hi=2)
+        _run_and_compare(A, B, inputs.BF16, sk.SK_POLICY_SK2_DP, None, 256, out_dtype=sk.SK_F32, exact=True)
 
 
 def _config5_all_policies(dtype):
